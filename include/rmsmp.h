@@ -1,0 +1,184 @@
+/*
+ * librmsmp -- row-wise mixed-scheme, multi-precision quantized GEMM for AMD MI355X (gfx950).
+ *
+ * Inference hot path of RMSMP (ICCV'21, arXiv 2111.00153): inside one layer every
+ * weight row (= filter, Fig. 1) carries its own quantization scheme and precision --
+ * Fixed-point 4-bit, Power-of-Two 4-bit or Fixed-point 8-bit (Section 3.1, 3.2, Fig. 2) --
+ * at a ratio that is the same in every layer (Section 3.2), and multiplies 4-bit Fixed
+ * activations (Section 3.1: activations are Fixed for all three schemes).
+ *
+ * Plain C ABI.  No C++ types, no exceptions and no torch types cross this boundary.
+ * Pointers are marked HOST or DEVICE.  Every call returns an rmsmp_status and never
+ * aborts; rmsmp_last_error() gives a thread-local message for the last failure.
+ * Calls that take a `stream` (a hipStream_t passed as void*, NULL = the null stream)
+ * only enqueue work: they do not synchronize and do not allocate.
+ */
+#ifndef RMSMP_H
+#define RMSMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  RMSMP_OK = 0,
+  RMSMP_EINVAL = 1,       /* NULL pointer, bad enum / flag value, misaligned buffer */
+  RMSMP_ESHAPE = 2,       /* sizes that do not fit together */
+  RMSMP_ENOMEM = 3,       /* host or device allocation failed */
+  RMSMP_EHIP = 4,         /* a HIP runtime call failed; see rmsmp_last_error() */
+  RMSMP_EUNSUPPORTED = 5, /* valid request this build has no kernel for */
+  RMSMP_EWORKSPACE = 6    /* workspace missing or too small */
+} rmsmp_status;
+
+/* Per-row scheme / precision code (the three candidates of Section 3.2, Fig. 2). */
+typedef enum { RMSMP_FIXED4 = 0, RMSMP_POT4 = 1, RMSMP_FIXED8 = 2 } rmsmp_scheme;
+
+/* Packed weights of one layer: opaque, owned by the library, lives in device memory. */
+typedef struct rmsmp_packed rmsmp_packed;
+
+const char* rmsmp_last_error(void);
+const char* rmsmp_version(void);
+
+/*
+ * Row counts for a layer-uniform ratio PoT-4 : Fixed-4 : Fixed-8 = A : B : C, A+B+C = 100
+ * (Section 4; Section 3.2 fixes C = 5).  Fixed-8 gets round(M*C/100) rows (at least one
+ * when C > 0), PoT-4 round(M*A/100), Fixed-4 the remainder.
+ * counts (HOST, 3 entries) = {n_fixed4, n_pot4, n_fixed8}, indexed by rmsmp_scheme.
+ */
+rmsmp_status rmsmp_ratio_counts(int64_t M, int32_t pct_pot4, int32_t pct_fixed4, int32_t pct_fixed8,
+                                int64_t counts[3]);
+
+/*
+ * Variance-based choice between PoT-4 and Fixed-4 (Alg. 1, else-branch; Section 3.1):
+ * rows whose entry in `scheme` is RMSMP_FIXED8 keep it; of the others, the n_pot4 rows
+ * with the lowest weight variance become RMSMP_POT4, the rest RMSMP_FIXED4 (ties by
+ * row index).  W: HOST fp32 [M][K].  scheme: HOST, M bytes, read and written.
+ */
+rmsmp_status rmsmp_assign_by_variance(const float* W, int64_t M, int64_t K, int64_t n_pot4,
+                                      uint8_t* scheme);
+
+/*
+ * Quantize, encode and upload the weights of one layer.
+ *
+ *   W       HOST fp32 [M][K], row-major; row r is filter r.  For a convolution
+ *           K = C*taps and the K index runs (c, kh, kw) -- the usual OIHW filter tensor.
+ *   scheme  HOST, M bytes, each an rmsmp_scheme.
+ *   alpha   HOST fp32 [M] or NULL.  NULL: alpha_r = max_k |W[r][k]| (an all-zero row
+ *           uses 1).  Weights outside [-alpha, alpha] are clipped (Section 3.1.1).
+ *   taps    KH*KW for a convolution layer, 1 for a plain GEMM layer.  K % taps == 0.
+ *   in_perm HOST int32 [K/taps] or NULL: the order in which the input channels arrive.
+ *           Channel position j of the activation tensor holds original channel in_perm[j]
+ *           (use the row permutation of the layer that produced the activations when that
+ *           layer wrote 4-bit output in grouped order).  NULL = identity.
+ *
+ * Row r is projected on its own level set with its own alpha:
+ *   Fixed-m (Eq. 1-2): q = round(Q * clip(w/alpha)), Q = 2^(m-1)-1, level alpha*q/Q;
+ *   PoT-4   (Eq. 3-4): level 0 or +-alpha*2^-k, k = 0..6, k = -round(log2 |clip(w/alpha)|),
+ *                      zero iff |clip| <= 2^-7;  rounding is half-to-even, all in fp32.
+ * Rows are grouped by scheme, 4-bit codes are nibble-packed, and the blob is copied to
+ * the current device (synchronously).  On success *out owns the device memory; release
+ * it with rmsmp_free_packed.  Errors: EINVAL (NULL, bad scheme code, alpha <= 0),
+ * ESHAPE (M, K < 1, K % taps), ENOMEM, EHIP.
+ */
+rmsmp_status rmsmp_pack_weights(const float* W, int64_t M, int64_t K, const uint8_t* scheme,
+                                const float* alpha, int32_t taps, const int32_t* in_perm,
+                                rmsmp_packed** out);
+
+void rmsmp_free_packed(rmsmp_packed* p);
+
+/*
+ * Describe a packed layer.  Any output pointer may be NULL.  The returned arrays are
+ * HOST memory borrowed from `p` (valid until rmsmp_free_packed):
+ *   counts[3]  rows per scheme {Fixed-4, PoT-4, Fixed-8}
+ *   perm       int32 [M]: grouped position g holds original row perm[g].  4-bit requantized
+ *              output (out_kind 2) is written in this grouped order.
+ *   rowscale   fp32 [M], original row order: level = rowscale * integer
+ *              (alpha/7, alpha*2^-6, alpha/127 for Fixed-4, PoT-4, Fixed-8)
+ *   rowsum     int32 [M], original row order: sum_k of the integer weights
+ */
+rmsmp_status rmsmp_packed_info(const rmsmp_packed* p, int64_t* M, int64_t* K, int64_t counts[3],
+                               const int32_t** perm, const float** rowscale, const int32_t** rowsum);
+
+/*
+ * Test hook: decode the device blob back to the integer weights.
+ * wint: HOST int8 [M][K], original row order and original K order; entry = integer level
+ * (Fixed-4: -7..7, PoT-4: 0 or +-2^(6-k), Fixed-8: -127..127).  Synchronizes the device.
+ */
+rmsmp_status rmsmp_unpack_codes(const rmsmp_packed* p, int8_t* wint);
+
+/*
+ * Test hook that needs no GPU: runs the host half of rmsmp_pack_weights (quantize, encode,
+ * group, lay out the blob) and decodes the blob again on the host.  Outputs (HOST, each may be
+ * NULL): wint int8 [M][K] as in rmsmp_unpack_codes; rowscale fp32 [M]; rowsum int32 [M];
+ * perm int32 [M] (grouped position -> original row).
+ */
+rmsmp_status rmsmp_pack_roundtrip_host(const float* W, int64_t M, int64_t K, const uint8_t* scheme,
+                                       const float* alpha, int32_t taps, const int32_t* in_perm,
+                                       int8_t* wint, float* rowscale, int32_t* rowsum, int32_t* perm);
+
+/*
+ * What happens to the int32 accumulator (fused into the GEMM kernel):
+ *   a = acc - act_zero_point * rowsum[r]                         (exact)
+ *   out_kind 0: Y = a                                              int32
+ *   out_kind 1: y = float(a) * (rowscale[r] * act_scale); y += bias[r]; relu -> Y = y   fp32
+ *   out_kind 2: q = clamp(round(y * out_inv_scale), 0, 15)          4-bit code, nibble-packed
+ * Every fp32 operation is rounded on its own (no fused multiply-add); round = half-to-even.
+ */
+typedef struct {
+  float act_scale;        /* s_x: real activation = s_x * (code - act_zero_point) */
+  int32_t act_zero_point; /* 0..15 for 4-bit codes, -128..127 for 8-bit codes */
+  int32_t act_bits;       /* 4: unsigned codes, two per byte; 8: signed int8 codes */
+  const float* bias;      /* DEVICE fp32 [M], original row order, or NULL */
+  int32_t relu;           /* 0 or 1 */
+  int32_t out_kind;       /* 0, 1 or 2 (see above) */
+  float out_inv_scale;    /* 1/s_out, used by out_kind 2 */
+} rmsmp_epilogue;
+
+/*
+ * Y = epilogue( W_packed . X ).           (Alg. 1 forward line: out = proj(input) . proj(W))
+ *
+ *   X  DEVICE, N columns of K codes, each column contiguous ("[N][K]"): act_bits 4 ->
+ *      K/2 bytes per column, element k in byte k/2, even k in the low nibble, K even;
+ *      act_bits 8 -> K int8 per column.  The K index is the one W was given in.  16-byte aligned.
+ *   Y  DEVICE, caller-allocated:
+ *        out_kind 0/1: [M][N] row-major, original row order (int32 / fp32)
+ *        out_kind 2:   [N][M/2] bytes; column n, grouped row g in byte g/2 (even g low nibble);
+ *                      M must be even.  This is exactly the X layout of a following layer.
+ *   stream  hipStream_t as void*.  Asynchronous; no allocation; no workspace needed.
+ * Errors: EINVAL, ESHAPE (N < 0, odd K with 4-bit codes, ...), EHIP.  N == 0 is a no-op.
+ */
+rmsmp_status rmsmp_gemm(const rmsmp_packed* Wp, const void* X, int64_t N, const rmsmp_epilogue* ep,
+                        void* Y, void* stream);
+
+/* Geometry of a 2-D convolution.  Output size OH = (H + 2*pad - KH)/stride + 1, same for OW. */
+typedef struct {
+  int32_t B, C, H, W, KH, KW, stride, pad;
+} rmsmp_conv_desc;
+
+/*
+ * Convolution lowered to the same GEMM by im2col (Fig. 1: filters of the weight tensor
+ * are rows of the weight matrix); the column index is n = (b*OH + oh)*OW + ow.
+ *
+ *   Wp  packed with K = C*KH*KW and taps = KH*KW.
+ *   X   DEVICE activation codes, NHWC: [B][H][W][C] (4-bit: C/2 bytes per pixel, C even).
+ *       Pixels outside the image count as real value 0, i.e. code act_zero_point.
+ *   Y   out_kind 0/1: [M][B*OH*OW];  out_kind 2: [B][OH][OW][M/2] bytes (NHWC, grouped rows).
+ *   workspace  DEVICE scratch of at least rmsmp_conv2d_workspace_size() bytes, or NULL when
+ *       that size is 0.  Layers whose C is a multiple of 64 (4-bit) run without workspace:
+ *       the im2col matrix is never materialised.  Other layers materialise it there.
+ * Errors: EINVAL, ESHAPE (K mismatch, empty output), EWORKSPACE, EHIP.
+ */
+rmsmp_status rmsmp_conv2d(const rmsmp_packed* Wp, const void* X, const rmsmp_conv_desc* d,
+                          const rmsmp_epilogue* ep, void* Y, void* workspace, size_t workspace_bytes,
+                          void* stream);
+
+rmsmp_status rmsmp_conv2d_workspace_size(const rmsmp_packed* Wp, const rmsmp_conv_desc* d,
+                                         int32_t act_bits, size_t* bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RMSMP_H */

@@ -1,0 +1,206 @@
+"""Thin ctypes binding of librmsmp.so: argument marshalling only.
+
+Function names mirror include/rmsmp.h.  Device buffers are torch tensors (PyTorch is used
+for device memory and streams, nothing else); host arrays are numpy.  Every computation of
+the hot path happens inside the library's HIP kernels -- there is no Python or CPU fallback:
+if the shared library is missing, importing this module raises.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+FIXED4, POT4, FIXED8 = 0, 1, 2
+OUT_INT32, OUT_FP32, OUT_U4 = 0, 1, 2
+
+_STATUS = {0: "OK", 1: "EINVAL", 2: "ESHAPE", 3: "ENOMEM", 4: "EHIP", 5: "EUNSUPPORTED", 6: "EWORKSPACE"}
+
+
+class RmsmpError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("librmsmp %s: %s" % (_STATUS.get(code, code), msg))
+        self.code = code
+
+
+class Epilogue(ctypes.Structure):
+    _fields_ = [("act_scale", ctypes.c_float), ("act_zero_point", ctypes.c_int32), ("act_bits", ctypes.c_int32),
+                ("bias", ctypes.c_void_p), ("relu", ctypes.c_int32), ("out_kind", ctypes.c_int32),
+                ("out_inv_scale", ctypes.c_float)]
+
+
+class ConvDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "C", "H", "W", "KH", "KW", "stride", "pad")]
+
+
+def _load():
+    path = _build.LIB
+    if not os.path.exists(path):
+        raise ImportError("librmsmp.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(there is no fallback implementation)")
+    lib = ctypes.CDLL(path)
+    lib.rmsmp_last_error.restype = ctypes.c_char_p
+    lib.rmsmp_version.restype = ctypes.c_char_p
+    return lib
+
+
+_lib = _load()
+
+EXPORTS = ["rmsmp_last_error", "rmsmp_version", "rmsmp_ratio_counts", "rmsmp_assign_by_variance",
+           "rmsmp_pack_weights", "rmsmp_free_packed", "rmsmp_packed_info", "rmsmp_unpack_codes",
+           "rmsmp_pack_roundtrip_host", "rmsmp_gemm", "rmsmp_conv2d", "rmsmp_conv2d_workspace_size"]
+
+
+def _check(rc):
+    if rc != 0:
+        raise RmsmpError(rc, _lib.rmsmp_last_error().decode())
+
+
+def _np(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _ptr(a):
+    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+
+
+def _dev(t):
+    """Device pointer of a torch tensor (must be contiguous and on the GPU)."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous GPU tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def rmsmp_version():
+    return _lib.rmsmp_version().decode()
+
+
+def rmsmp_ratio_counts(M, pct_pot4, pct_fixed4, pct_fixed8):
+    c = (ctypes.c_int64 * 3)()
+    _check(_lib.rmsmp_ratio_counts(ctypes.c_int64(M), int(pct_pot4), int(pct_fixed4), int(pct_fixed8), c))
+    return int(c[0]), int(c[1]), int(c[2])
+
+
+def rmsmp_assign_by_variance(W, scheme, n_pot4):
+    W = _np(W, np.float32)
+    s = _np(scheme, np.uint8).copy()
+    _check(_lib.rmsmp_assign_by_variance(_ptr(W), ctypes.c_int64(W.shape[0]), ctypes.c_int64(W.shape[1]),
+                                         ctypes.c_int64(n_pot4), _ptr(s)))
+    return s
+
+
+class Packed:
+    """Owner of an rmsmp_packed handle."""
+
+    def __init__(self, handle, M, K, taps):
+        self.handle = handle
+        self.M, self.K, self.taps = M, K, taps
+        counts = (ctypes.c_int64 * 3)()
+        perm = ctypes.POINTER(ctypes.c_int32)()
+        rs = ctypes.POINTER(ctypes.c_float)()
+        rsum = ctypes.POINTER(ctypes.c_int32)()
+        _check(_lib.rmsmp_packed_info(handle, None, None, counts, ctypes.byref(perm), ctypes.byref(rs),
+                                      ctypes.byref(rsum)))
+        self.counts = tuple(int(c) for c in counts)
+        self.perm = np.ctypeslib.as_array(perm, (M,)).copy()
+        self.rowscale = np.ctypeslib.as_array(rs, (M,)).copy()
+        self.rowsum = np.ctypeslib.as_array(rsum, (M,)).copy()
+
+    def free(self):
+        if self.handle:
+            _lib.rmsmp_free_packed(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def rmsmp_pack_weights(W, scheme, alpha=None, taps=1, in_perm=None):
+    W = _np(W, np.float32)
+    M, K = W.shape
+    scheme = _np(scheme, np.uint8)
+    if scheme.shape != (M,):
+        raise ValueError("scheme must have one entry per row")
+    alpha = None if alpha is None else _np(alpha, np.float32)
+    in_perm = None if in_perm is None else _np(in_perm, np.int32)
+    h = ctypes.c_void_p()
+    _check(_lib.rmsmp_pack_weights(_ptr(W), ctypes.c_int64(M), ctypes.c_int64(K), _ptr(scheme), _ptr(alpha),
+                                   ctypes.c_int32(taps), _ptr(in_perm), ctypes.byref(h)))
+    return Packed(h, M, K, taps)
+
+
+def rmsmp_unpack_codes(p):
+    out = np.empty((p.M, p.K), np.int8)
+    _check(_lib.rmsmp_unpack_codes(p.handle, _ptr(out)))
+    return out
+
+
+def rmsmp_pack_roundtrip_host(W, scheme, alpha=None, taps=1, in_perm=None):
+    """No GPU needed.  Returns dict(wint, rowscale, rowsum, perm)."""
+    W = _np(W, np.float32)
+    M, K = W.shape
+    scheme = _np(scheme, np.uint8)
+    alpha = None if alpha is None else _np(alpha, np.float32)
+    in_perm = None if in_perm is None else _np(in_perm, np.int32)
+    wint = np.empty((M, K), np.int8)
+    rowscale = np.empty(M, np.float32)
+    rowsum = np.empty(M, np.int32)
+    perm = np.empty(M, np.int32)
+    _check(_lib.rmsmp_pack_roundtrip_host(_ptr(W), ctypes.c_int64(M), ctypes.c_int64(K), _ptr(scheme), _ptr(alpha),
+                                          ctypes.c_int32(taps), _ptr(in_perm), _ptr(wint), _ptr(rowscale),
+                                          _ptr(rowsum), _ptr(perm)))
+    return dict(wint=wint, rowscale=rowscale, rowsum=rowsum, perm=perm)
+
+
+def make_epilogue(act_scale=1.0, act_zero_point=0, act_bits=4, bias=None, relu=False, out_kind=OUT_INT32,
+                  out_inv_scale=1.0):
+    return Epilogue(float(act_scale), int(act_zero_point), int(act_bits),
+                    None if bias is None else bias.data_ptr(), 1 if relu else 0, int(out_kind),
+                    float(out_inv_scale))
+
+
+def rmsmp_gemm(p, X, N, ep, Y, stream=None):
+    _check(_lib.rmsmp_gemm(p.handle, _dev(X), ctypes.c_int64(N), ctypes.byref(ep), _dev(Y), _stream(stream)))
+
+
+def rmsmp_conv2d_workspace_size(p, d, act_bits=4):
+    n = ctypes.c_size_t()
+    _check(_lib.rmsmp_conv2d_workspace_size(p.handle, ctypes.byref(d), ctypes.c_int32(act_bits), ctypes.byref(n)))
+    return int(n.value)
+
+
+def rmsmp_conv2d(p, X, d, ep, Y, workspace=None, stream=None):
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib.rmsmp_conv2d(p.handle, _dev(X), ctypes.byref(d), ctypes.byref(ep), _dev(Y), _dev(workspace),
+                             ctypes.c_size_t(wbytes), _stream(stream)))
+
+
+# ---- storage helpers for callers (nibble packing of activation codes; no arithmetic of the method)
+
+def pack_u4(codes):
+    """uint8 codes (..., K) with values 0..15 -> (..., K/2) bytes, even index in the low nibble."""
+    c = np.ascontiguousarray(codes, dtype=np.uint8)
+    if c.shape[-1] % 2:
+        raise ValueError("last dimension must be even")
+    return (c[..., 0::2] | (c[..., 1::2] << 4)).astype(np.uint8)
+
+
+def unpack_u4(b):
+    b = np.ascontiguousarray(b, dtype=np.uint8)
+    out = np.empty(b.shape[:-1] + (b.shape[-1] * 2,), np.uint8)
+    out[..., 0::2] = b & 15
+    out[..., 1::2] = b >> 4
+    return out

@@ -1,0 +1,300 @@
+// C-ABI glue of librmsmp: argument checking, device memory of packed layers, kernel dispatch.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "rmsmp_internal.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+rmsmp_status fail(rmsmp_status s, const std::string& msg) {
+  g_err = msg;
+  return s;
+}
+
+rmsmp_status hip_fail(hipError_t e, const char* what) {
+  g_err = std::string(what) + ": " + hipGetErrorString(e);
+  return RMSMP_EHIP;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+rmsmp_status check_epilogue(const rmsmp_epilogue* ep, int64_t M) {
+  if (!ep) return fail(RMSMP_EINVAL, "epilogue is NULL");
+  if (ep->act_bits != 4 && ep->act_bits != 8) return fail(RMSMP_EINVAL, "act_bits must be 4 or 8");
+  if (ep->out_kind < 0 || ep->out_kind > 2) return fail(RMSMP_EINVAL, "out_kind must be 0, 1 or 2");
+  if (ep->relu != 0 && ep->relu != 1) return fail(RMSMP_EINVAL, "relu must be 0 or 1");
+  if (ep->act_bits == 4 && (ep->act_zero_point < 0 || ep->act_zero_point > 15))
+    return fail(RMSMP_EINVAL, "act_zero_point must be in 0..15 for 4-bit codes");
+  if (ep->act_bits == 8 && (ep->act_zero_point < -128 || ep->act_zero_point > 127))
+    return fail(RMSMP_EINVAL, "act_zero_point must be in -128..127 for 8-bit codes");
+  if (ep->out_kind == 2 && (M & 1)) return fail(RMSMP_ESHAPE, "4-bit output needs an even number of rows");
+  return RMSMP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* rmsmp_last_error(void) { return g_err.c_str(); }
+
+const char* rmsmp_version(void) { return "librmsmp 0.1 (gfx950)"; }
+
+rmsmp_status rmsmp_ratio_counts(int64_t M, int32_t pct_pot4, int32_t pct_fixed4, int32_t pct_fixed8,
+                                int64_t counts[3]) {
+  rmsmp_status s = rmsmp::ratio_counts(M, pct_pot4, pct_fixed4, pct_fixed8, counts);
+  if (s != RMSMP_OK) return fail(s, "ratio_counts: percentages must be non-negative and sum to 100");
+  return s;
+}
+
+rmsmp_status rmsmp_assign_by_variance(const float* W, int64_t M, int64_t K, int64_t n_pot4, uint8_t* scheme) {
+  rmsmp_status s = rmsmp::assign_by_variance(W, M, K, n_pot4, scheme);
+  if (s != RMSMP_OK) return fail(s, "assign_by_variance: bad argument");
+  return s;
+}
+
+rmsmp_status rmsmp_pack_weights(const float* W, int64_t M, int64_t K, const uint8_t* scheme, const float* alpha,
+                                int32_t taps, const int32_t* in_perm, rmsmp_packed** out) {
+  if (!out) return fail(RMSMP_EINVAL, "pack_weights: out is NULL");
+  *out = nullptr;
+  rmsmp_packed* p = new (std::nothrow) rmsmp_packed();
+  if (!p) return fail(RMSMP_ENOMEM, "pack_weights: host allocation failed");
+  std::string err;
+  rmsmp_status st;
+  try {
+    st = rmsmp::pack_host(W, M, K, scheme, alpha, taps, in_perm, &p->host, &err);
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return fail(RMSMP_ENOMEM, "pack_weights: host allocation failed");
+  }
+  if (st != RMSMP_OK) {
+    delete p;
+    return fail(st, err);
+  }
+  const rmsmp::HostPacked& h = p->host;
+  // one device allocation: blob | tiles | rowscale | rowsum | orig | gpos | lut
+  const size_t n_blob = align_up(h.blob.size(), 256);
+  const size_t n_tiles = align_up(h.tiles.size() * sizeof(rmsmp::TileDesc), 256);
+  const size_t n_rows = align_up(h.p_rowscale.size() * 4, 256);
+  const size_t n_lut = align_up(h.p_lut.size() * 4, 256);
+  const size_t total = n_blob + n_tiles + 4 * n_rows + n_lut;
+  hipError_t e = hipGetDevice(&p->device);
+  if (e != hipSuccess) {
+    delete p;
+    return hip_fail(e, "hipGetDevice");
+  }
+  e = hipMalloc(&p->dev_alloc, total);
+  if (e != hipSuccess) {
+    delete p;
+    g_err = std::string("pack_weights: hipMalloc: ") + hipGetErrorString(e);
+    return RMSMP_ENOMEM;
+  }
+  p->dev_bytes = total;
+  uint8_t* base = (uint8_t*)p->dev_alloc;
+  size_t off = 0;
+  auto put = [&](const void* src, size_t bytes, size_t reserved) -> const uint8_t* {
+    uint8_t* dst = base + off;
+    if (bytes && e == hipSuccess) e = hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice);
+    off += reserved;
+    return dst;
+  };
+  p->dev.blob = put(h.blob.data(), h.blob.size(), n_blob);
+  p->dev.tiles = (const rmsmp::TileDesc*)put(h.tiles.data(), h.tiles.size() * sizeof(rmsmp::TileDesc), n_tiles);
+  p->dev.p_rowscale = (const float*)put(h.p_rowscale.data(), h.p_rowscale.size() * 4, n_rows);
+  p->dev.p_rowsum = (const int32_t*)put(h.p_rowsum.data(), h.p_rowsum.size() * 4, n_rows);
+  p->dev.p_orig = (const int32_t*)put(h.p_orig.data(), h.p_orig.size() * 4, n_rows);
+  p->dev.p_gpos = (const int32_t*)put(h.p_gpos.data(), h.p_gpos.size() * 4, n_rows);
+  p->dev.p_lut = (const uint32_t*)put(h.p_lut.data(), h.p_lut.size() * 4, n_lut);
+  p->dev.n_tiles = (int32_t)h.tiles.size();
+  p->dev.nks = (int32_t)h.nks;
+  if (e != hipSuccess) {
+    (void)hipFree(p->dev_alloc);
+    delete p;
+    return hip_fail(e, "pack_weights: hipMemcpy");
+  }
+  // the host copy of the blob is not needed any more
+  std::vector<uint8_t>().swap(p->host.blob);
+  *out = p;
+  return RMSMP_OK;
+}
+
+rmsmp_status rmsmp_pack_roundtrip_host(const float* W, int64_t M, int64_t K, const uint8_t* scheme,
+                                       const float* alpha, int32_t taps, const int32_t* in_perm, int8_t* wint,
+                                       float* rowscale, int32_t* rowsum, int32_t* perm) {
+  rmsmp::HostPacked h;
+  std::string err;
+  rmsmp_status st;
+  try {
+    st = rmsmp::pack_host(W, M, K, scheme, alpha, taps, in_perm, &h, &err);
+  } catch (const std::bad_alloc&) {
+    return fail(RMSMP_ENOMEM, "pack_roundtrip_host: host allocation failed");
+  }
+  if (st != RMSMP_OK) return fail(st, err);
+  if (wint) {
+    std::memset(wint, 0, (size_t)M * (size_t)K);
+    rmsmp::unpack_host(h, h.blob.data(), wint);
+  }
+  if (rowscale) std::memcpy(rowscale, h.rowscale.data(), (size_t)M * 4);
+  if (rowsum) std::memcpy(rowsum, h.rowsum.data(), (size_t)M * 4);
+  if (perm) std::memcpy(perm, h.perm.data(), (size_t)M * 4);
+  return RMSMP_OK;
+}
+
+void rmsmp_free_packed(rmsmp_packed* p) {
+  if (!p) return;
+  if (p->dev_alloc) (void)hipFree(p->dev_alloc);
+  delete p;
+}
+
+rmsmp_status rmsmp_packed_info(const rmsmp_packed* p, int64_t* M, int64_t* K, int64_t counts[3],
+                               const int32_t** perm, const float** rowscale, const int32_t** rowsum) {
+  if (!p) return fail(RMSMP_EINVAL, "packed_info: NULL handle");
+  if (M) *M = p->host.M;
+  if (K) *K = p->host.K;
+  if (counts)
+    for (int i = 0; i < 3; ++i) counts[i] = p->host.counts[i];
+  if (perm) *perm = p->host.perm.data();
+  if (rowscale) *rowscale = p->host.rowscale.data();
+  if (rowsum) *rowsum = p->host.rowsum.data();
+  return RMSMP_OK;
+}
+
+rmsmp_status rmsmp_unpack_codes(const rmsmp_packed* p, int8_t* wint) {
+  if (!p || !wint) return fail(RMSMP_EINVAL, "unpack_codes: NULL argument");
+  size_t blob_bytes = 0;
+  for (const auto& t : p->host.tiles)
+    blob_bytes += (size_t)p->host.nks * rmsmp::LANES * (t.kind == rmsmp::TILE_I8 ? 16 : 8);
+  std::vector<uint8_t> blob;
+  try {
+    blob.resize(blob_bytes);
+  } catch (const std::bad_alloc&) {
+    return fail(RMSMP_ENOMEM, "unpack_codes: host allocation failed");
+  }
+  hipError_t e = hipDeviceSynchronize();
+  if (e == hipSuccess && blob_bytes) e = hipMemcpy(blob.data(), p->dev.blob, blob_bytes, hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_fail(e, "unpack_codes: hipMemcpy");
+  std::memset(wint, 0, (size_t)p->host.M * (size_t)p->host.K);
+  rmsmp::unpack_host(p->host, blob.data(), wint);
+  return RMSMP_OK;
+}
+
+rmsmp_status rmsmp_gemm(const rmsmp_packed* Wp, const void* X, int64_t N, const rmsmp_epilogue* ep, void* Y,
+                        void* stream) {
+  if (!Wp) return fail(RMSMP_EINVAL, "gemm: NULL packed weights");
+  rmsmp_status st = check_epilogue(ep, Wp->host.M);
+  if (st != RMSMP_OK) return st;
+  if (N < 0) return fail(RMSMP_ESHAPE, "gemm: N < 0");
+  if (N == 0) return RMSMP_OK;
+  if (!X || !Y) return fail(RMSMP_EINVAL, "gemm: NULL X or Y");
+  if (ep->act_bits == 4 && (Wp->host.K & 1)) return fail(RMSMP_ESHAPE, "gemm: 4-bit activations need an even K");
+  if (((uintptr_t)X & 15) != 0) return fail(RMSMP_EINVAL, "gemm: X must be 16-byte aligned");
+  if (N > (int64_t)0x7fffffff * 64) return fail(RMSMP_ESHAPE, "gemm: N too large");
+  rmsmp::GemmArgs a;
+  a.w = Wp->dev;
+  a.M = Wp->host.M;
+  a.K = Wp->host.K;
+  a.N = N;
+  a.X = X;
+  a.Y = Y;
+  a.ep = *ep;
+  a.conv = 0;
+  hipError_t e = (hipError_t)rmsmp::launch_gemm(a, stream);
+  if (e != hipSuccess) return hip_fail(e, "gemm: kernel launch");
+  return RMSMP_OK;
+}
+
+static rmsmp_status conv_geometry(const rmsmp_packed* Wp, const rmsmp_conv_desc* d, int32_t act_bits, int* OH,
+                                  int* OW) {
+  if (!Wp || !d) return fail(RMSMP_EINVAL, "conv2d: NULL argument");
+  if (d->B < 1 || d->C < 1 || d->H < 1 || d->W < 1 || d->KH < 1 || d->KW < 1 || d->stride < 1 || d->pad < 0)
+    return fail(RMSMP_ESHAPE, "conv2d: bad geometry");
+  if ((int64_t)d->C * d->KH * d->KW != Wp->host.K || d->KH * d->KW != Wp->host.taps)
+    return fail(RMSMP_ESHAPE, "conv2d: C*KH*KW and KH*KW must match the packed layer's K and taps");
+  if (act_bits == 4 && (d->C & 1)) return fail(RMSMP_ESHAPE, "conv2d: 4-bit activations need an even C");
+  const int oh = (d->H + 2 * d->pad - d->KH) / d->stride + 1;
+  const int ow = (d->W + 2 * d->pad - d->KW) / d->stride + 1;
+  if (d->H + 2 * d->pad < d->KH || d->W + 2 * d->pad < d->KW || oh < 1 || ow < 1)
+    return fail(RMSMP_ESHAPE, "conv2d: empty output");
+  *OH = oh;
+  *OW = ow;
+  return RMSMP_OK;
+}
+
+static bool conv_is_implicit(const rmsmp_conv_desc* d) { return d->C % rmsmp::KSTEP == 0; }
+
+rmsmp_status rmsmp_conv2d_workspace_size(const rmsmp_packed* Wp, const rmsmp_conv_desc* d, int32_t act_bits,
+                                         size_t* bytes) {
+  if (!bytes) return fail(RMSMP_EINVAL, "conv2d_workspace_size: NULL bytes");
+  if (act_bits != 4 && act_bits != 8) return fail(RMSMP_EINVAL, "act_bits must be 4 or 8");
+  int OH, OW;
+  rmsmp_status st = conv_geometry(Wp, d, act_bits, &OH, &OW);
+  if (st != RMSMP_OK) return st;
+  if (conv_is_implicit(d)) {
+    *bytes = 0;
+    return RMSMP_OK;
+  }
+  const size_t N = (size_t)d->B * OH * OW;
+  const size_t row = act_bits == 4 ? (size_t)Wp->host.Kpad / 2 : (size_t)Wp->host.Kpad;
+  *bytes = align_up(N * row, 256);
+  return RMSMP_OK;
+}
+
+rmsmp_status rmsmp_conv2d(const rmsmp_packed* Wp, const void* X, const rmsmp_conv_desc* d,
+                          const rmsmp_epilogue* ep, void* Y, void* workspace, size_t workspace_bytes,
+                          void* stream) {
+  if (!Wp) return fail(RMSMP_EINVAL, "conv2d: NULL packed weights");
+  rmsmp_status st = check_epilogue(ep, Wp->host.M);
+  if (st != RMSMP_OK) return st;
+  int OH, OW;
+  st = conv_geometry(Wp, d, ep->act_bits, &OH, &OW);
+  if (st != RMSMP_OK) return st;
+  if (!X || !Y) return fail(RMSMP_EINVAL, "conv2d: NULL X or Y");
+  if (((uintptr_t)X & 15) != 0) return fail(RMSMP_EINVAL, "conv2d: X must be 16-byte aligned");
+  const int64_t N = (int64_t)d->B * OH * OW;
+  rmsmp::GemmArgs a;
+  a.w = Wp->dev;
+  a.M = Wp->host.M;
+  a.N = N;
+  a.Y = Y;
+  a.ep = *ep;
+  a.d = *d;
+  a.OH = OH;
+  a.OW = OW;
+  if (conv_is_implicit(d)) {
+    a.K = Wp->host.K;
+    a.X = X;
+    a.conv = 1;
+  } else {
+    size_t need = 0;
+    st = rmsmp_conv2d_workspace_size(Wp, d, ep->act_bits, &need);
+    if (st != RMSMP_OK) return st;
+    if (!workspace || workspace_bytes < need)
+      return fail(RMSMP_EWORKSPACE, "conv2d: workspace of " + std::to_string(need) + " bytes required");
+    if (((uintptr_t)workspace & 15) != 0) return fail(RMSMP_EINVAL, "conv2d: workspace must be 16-byte aligned");
+    rmsmp::Im2colArgs ia;
+    ia.X = X;
+    ia.cols = workspace;
+    ia.d = *d;
+    ia.OH = OH;
+    ia.OW = OW;
+    ia.N = N;
+    ia.K = Wp->host.K;
+    ia.Kpad = Wp->host.Kpad;
+    ia.act_bits = ep->act_bits;
+    ia.zero_point = ep->act_zero_point;
+    hipError_t e = (hipError_t)rmsmp::launch_im2col(ia, stream);
+    if (e != hipSuccess) return hip_fail(e, "conv2d: im2col launch");
+    a.K = Wp->host.Kpad;
+    a.X = workspace;
+    a.conv = 0;
+  }
+  hipError_t e = (hipError_t)rmsmp::launch_gemm(a, stream);
+  if (e != hipSuccess) return hip_fail(e, "conv2d: kernel launch");
+  return RMSMP_OK;
+}
+
+}  // extern "C"

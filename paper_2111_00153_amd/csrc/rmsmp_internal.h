@@ -1,0 +1,114 @@
+// Internal declarations shared by the host packer, the kernels and the C-ABI glue.
+// Not installed; the public interface is include/rmsmp.h.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "rmsmp.h"
+
+namespace rmsmp {
+
+// A weight tile is TILE_M consecutive rows of one storage class; the K axis is cut in
+// steps of KSTEP elements, the depth of one v_mfma_i32_16x16x64_i8.
+constexpr int TILE_M = 16;
+constexpr int KSTEP = 64;
+constexpr int LANES = 64;
+
+// How a tile's codes are stored and decoded in registers.
+enum TileKind : int32_t {
+  TILE_NIB_SHIFT = 0,  // 4-bit two's-complement codes; decode = mask/shift, yields 16*q
+  TILE_NIB_LUT = 1,    // 4-bit codes through a per-row 16-entry byte table (PoT-4 exponent codes)
+  TILE_I8 = 2          // 8-bit codes, no decode (Fixed-8)
+};
+
+struct TileDesc {
+  int32_t kind;      // TileKind
+  int32_t nvalid;    // rows of the tile that are real (the rest is zero padding)
+  int32_t g0;        // grouped position of the tile's first row
+  int32_t reserved;
+  int64_t blob_off;  // byte offset of the tile in the blob
+};
+
+// Within a run of 16 consecutive K elements the MFMA operand slot s holds element kSlot[s]:
+// the order that mask/shift nibble extraction produces (even elements of each 8, then odd).
+constexpr int kSlot[16] = {0, 2, 4, 6, 1, 3, 5, 7, 8, 10, 12, 14, 9, 11, 13, 15};
+
+struct HostPacked {
+  int64_t M = 0, K = 0, C = 0;
+  int32_t taps = 1;
+  int64_t Kpad = 0, nks = 0;
+  int64_t counts[3] = {0, 0, 0};
+  std::vector<int32_t> perm;       // [M] grouped position -> original row
+  std::vector<float> rowscale;     // [M] original order
+  std::vector<int32_t> rowsum;     // [M] original order
+  std::vector<uint8_t> scheme;     // [M] original order
+  std::vector<int32_t> kmap;       // [K] internal k -> original k
+  std::vector<TileDesc> tiles;
+  // tables indexed by padded row p = tile*TILE_M + r
+  std::vector<float> p_rowscale;
+  std::vector<int32_t> p_rowsum, p_orig, p_gpos;
+  std::vector<uint32_t> p_lut;     // 4 words per padded row
+  std::vector<uint8_t> blob;
+};
+
+// Host side of rmsmp_pack_weights: quantize, encode, group, lay out.  Returns RMSMP_OK or an
+// error with `err` filled.
+rmsmp_status pack_host(const float* W, int64_t M, int64_t K, const uint8_t* scheme, const float* alpha,
+                       int32_t taps, const int32_t* in_perm, HostPacked* out, std::string* err);
+
+// Decode a blob (as laid out by pack_host) back to integer weights in original order.
+void unpack_host(const HostPacked& hp, const uint8_t* blob, int8_t* wint);
+
+rmsmp_status ratio_counts(int64_t M, int32_t a, int32_t b, int32_t c, int64_t counts[3]);
+rmsmp_status assign_by_variance(const float* W, int64_t M, int64_t K, int64_t n_pot4, uint8_t* scheme);
+
+// Device-side view handed to the kernels.
+struct DevicePacked {
+  const uint8_t* blob = nullptr;
+  const TileDesc* tiles = nullptr;
+  const float* p_rowscale = nullptr;
+  const int32_t* p_rowsum = nullptr;
+  const int32_t* p_orig = nullptr;
+  const int32_t* p_gpos = nullptr;
+  const uint32_t* p_lut = nullptr;
+  int32_t n_tiles = 0;
+  int32_t nks = 0;
+};
+
+struct GemmArgs {
+  DevicePacked w;
+  int64_t M = 0, K = 0, N = 0;
+  const void* X = nullptr;
+  void* Y = nullptr;
+  rmsmp_epilogue ep{};
+  // convolution (implicit im2col); conv == 0 for a plain GEMM
+  int32_t conv = 0;
+  rmsmp_conv_desc d{};
+  int32_t OH = 0, OW = 0;
+};
+
+struct Im2colArgs {
+  const void* X = nullptr;
+  void* cols = nullptr;  // [N][Kpad/2] (4-bit) or [N][Kpad] (8-bit), internal K order (tap, c)
+  rmsmp_conv_desc d{};
+  int32_t OH = 0, OW = 0;
+  int64_t N = 0, K = 0, Kpad = 0;
+  int32_t act_bits = 4;
+  int32_t zero_point = 0;
+};
+
+// Kernel launchers (kernels.hip).  Return hipError_t as int.
+int launch_gemm(const GemmArgs& a, void* stream);
+int launch_im2col(const Im2colArgs& a, void* stream);
+
+}  // namespace rmsmp
+
+struct rmsmp_packed {
+  rmsmp::HostPacked host;
+  rmsmp::DevicePacked dev;
+  void* dev_alloc = nullptr;  // one allocation holding every device table
+  size_t dev_bytes = 0;
+  int device = 0;
+};
