@@ -167,7 +167,7 @@ typedef struct {
  *       Pixels outside the image count as real value 0, i.e. code act_zero_point.
  *   Y   out_kind 0/1: [M][B*OH*OW];  out_kind 2: [B][OH][OW][M/2] bytes (NHWC, grouped rows).
  *   workspace  DEVICE scratch of at least rmsmp_conv2d_workspace_size() bytes, or NULL when
- *       that size is 0.  Layers whose C is a multiple of 64 (4-bit) run without workspace:
+ *       that size is 0.  Layers whose C is a multiple of 16 run without workspace:
  *       the im2col matrix is never materialised.  Other layers materialise it there.
  * Errors: EINVAL, ESHAPE (K mismatch, empty output), EWORKSPACE, EHIP.
  */

@@ -188,6 +188,34 @@ def rmsmp_conv2d(p, X, d, ep, Y, workspace=None, stream=None):
                              ctypes.c_size_t(wbytes), _stream(stream)))
 
 
+def conv2d_launcher(p, X, d, ep, Y, workspace=None, stream=None):
+    """rmsmp_conv2d with the arguments marshalled once: returns a zero-argument callable that
+    enqueues the same call again (for launch-bound loops and graph capture)."""
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    args = (p.handle, _dev(X), ctypes.byref(d), ctypes.byref(ep), _dev(Y), _dev(workspace),
+            ctypes.c_size_t(wbytes), _stream(stream))
+    fn = _lib.rmsmp_conv2d
+
+    def launch():
+        rc = fn(*args)
+        if rc:
+            _check(rc)
+    launch.keepalive = (p, X, d, ep, Y, workspace)
+    return launch
+
+
+def gemm_launcher(p, X, N, ep, Y, stream=None):
+    args = (p.handle, _dev(X), ctypes.c_int64(N), ctypes.byref(ep), _dev(Y), _stream(stream))
+    fn = _lib.rmsmp_gemm
+
+    def launch():
+        rc = fn(*args)
+        if rc:
+            _check(rc)
+    launch.keepalive = (p, X, ep, Y)
+    return launch
+
+
 # ---- storage helpers for callers (nibble packing of activation codes; no arithmetic of the method)
 
 def pack_u4(codes):

@@ -76,12 +76,12 @@ rmsmp_status rmsmp_pack_weights(const float* W, int64_t M, int64_t K, const uint
     return fail(st, err);
   }
   const rmsmp::HostPacked& h = p->host;
-  // one device allocation: blob | tiles | rowscale | rowsum | orig | gpos | lut
+  // one device allocation: blob | tiles | row metadata | lut
   const size_t n_blob = align_up(h.blob.size(), 256);
   const size_t n_tiles = align_up(h.tiles.size() * sizeof(rmsmp::TileDesc), 256);
-  const size_t n_rows = align_up(h.p_rowscale.size() * 4, 256);
+  const size_t n_meta = align_up(h.p_meta.size() * 4, 256);
   const size_t n_lut = align_up(h.p_lut.size() * 4, 256);
-  const size_t total = n_blob + n_tiles + 4 * n_rows + n_lut;
+  const size_t total = n_blob + n_tiles + n_meta + n_lut;
   hipError_t e = hipGetDevice(&p->device);
   if (e != hipSuccess) {
     delete p;
@@ -104,10 +104,7 @@ rmsmp_status rmsmp_pack_weights(const float* W, int64_t M, int64_t K, const uint
   };
   p->dev.blob = put(h.blob.data(), h.blob.size(), n_blob);
   p->dev.tiles = (const rmsmp::TileDesc*)put(h.tiles.data(), h.tiles.size() * sizeof(rmsmp::TileDesc), n_tiles);
-  p->dev.p_rowscale = (const float*)put(h.p_rowscale.data(), h.p_rowscale.size() * 4, n_rows);
-  p->dev.p_rowsum = (const int32_t*)put(h.p_rowsum.data(), h.p_rowsum.size() * 4, n_rows);
-  p->dev.p_orig = (const int32_t*)put(h.p_orig.data(), h.p_orig.size() * 4, n_rows);
-  p->dev.p_gpos = (const int32_t*)put(h.p_gpos.data(), h.p_gpos.size() * 4, n_rows);
+  p->dev.p_meta = (const int32_t*)put(h.p_meta.data(), h.p_meta.size() * 4, n_meta);
   p->dev.p_lut = (const uint32_t*)put(h.p_lut.data(), h.p_lut.size() * 4, n_lut);
   p->dev.n_tiles = (int32_t)h.tiles.size();
   p->dev.nks = (int32_t)h.nks;
@@ -224,7 +221,8 @@ static rmsmp_status conv_geometry(const rmsmp_packed* Wp, const rmsmp_conv_desc*
   return RMSMP_OK;
 }
 
-static bool conv_is_implicit(const rmsmp_conv_desc* d) { return d->C % rmsmp::KSTEP == 0; }
+// im2col is done on the fly whenever a 16-channel chunk is one aligned load
+static bool conv_is_implicit(const rmsmp_conv_desc* d) { return d->C % 16 == 0; }
 
 rmsmp_status rmsmp_conv2d_workspace_size(const rmsmp_packed* Wp, const rmsmp_conv_desc* d, int32_t act_bits,
                                          size_t* bytes) {

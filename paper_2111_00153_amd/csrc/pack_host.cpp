@@ -148,7 +148,7 @@ rmsmp_status pack_host(const float* W, int64_t M, int64_t K, const uint8_t* sche
   hp->K = K;
   hp->C = C;
   hp->taps = taps;
-  hp->Kpad = (K + KSTEP - 1) / KSTEP * KSTEP;
+  hp->Kpad = (K + KPAD_UNIT - 1) / KPAD_UNIT * KPAD_UNIT;
   hp->nks = hp->Kpad / KSTEP;
 
   // internal K order: (tap, channel position) -> original (channel, tap)
@@ -215,26 +215,30 @@ rmsmp_status pack_host(const float* W, int64_t M, int64_t K, const uint8_t* sche
   }
 
   // 2. storage class per row.  Fixed-4 rows decode by mask/shift, PoT-4 rows through the byte
-  // table, Fixed-8 rows are stored as bytes.  The 4-bit requantized output packs two grouped
-  // rows per byte, so every class must start at an even grouped position: when a class has an
-  // odd number of rows its last row is stored in the next, more general class (a Fixed-4 row
-  // decodes fine through a table, any 4-bit row fits a byte).  Levels and scales do not change.
+  // table, Fixed-8 rows are stored as bytes.  A class whose row count is not a multiple of the
+  // tile height hands its last (count % TILE_M) rows to the next, more general class when one
+  // follows: a Fixed-4 row decodes fine through a table and any 4-bit row fits a byte.  Levels
+  // and scales do not change, and the layer needs ceil(M / TILE_M) tiles instead of up to two more.
+  // Every class then starts at a multiple of TILE_M in grouped order (two grouped rows share
+  // one byte of the 4-bit output, so class boundaries must at least be even).
   std::vector<int32_t> cls((size_t)M);
   for (int64_t r = 0; r < M; ++r)
     cls[(size_t)r] = scheme[r] == RMSMP_FIXED4 ? TILE_NIB_SHIFT : scheme[r] == RMSMP_POT4 ? TILE_NIB_LUT : TILE_I8;
   int64_t n_cls[3] = {hp->counts[0], hp->counts[1], hp->counts[2]};
   for (int c = 0; c < 2; ++c) {
-    if (!(n_cls[c] & 1)) continue;
+    int64_t spill = n_cls[c] % TILE_M;
+    if (spill == 0) continue;
     bool later = false;
     for (int c2 = c + 1; c2 < 3; ++c2) later = later || n_cls[c2] > 0;
-    if (!later) continue;  // the last class may stay odd (then M itself is odd)
-    for (int64_t r = M - 1; r >= 0; --r)
+    if (!later) continue;  // nothing follows: the last tile of this class is padded instead
+    const int next = c + 1;
+    for (int64_t r = M - 1; r >= 0 && spill > 0; --r)
       if (cls[(size_t)r] == c) {
-        cls[(size_t)r] = c + 1;
-        break;
+        cls[(size_t)r] = next;
+        --spill;
+        n_cls[c] -= 1;
+        n_cls[next] += 1;
       }
-    n_cls[c] -= 1;
-    n_cls[c + 1] += 1;
   }
 
   // 3. grouped order and tiles
@@ -260,6 +264,8 @@ rmsmp_status pack_host(const float* W, int64_t M, int64_t K, const uint8_t* sche
   hp->p_orig.assign((size_t)Mpad, -1);
   hp->p_gpos.assign((size_t)Mpad, -1);
   hp->p_lut.assign((size_t)Mpad * 4, 0u);
+  hp->p_meta.assign((size_t)Mpad * 4, 0);
+  for (int64_t p = 0; p < Mpad; ++p) hp->p_meta[(size_t)p * 4 + 2] = hp->p_meta[(size_t)p * 4 + 3] = -1;
 
   int64_t off = 0;
   for (auto& td : hp->tiles) {
@@ -268,17 +274,26 @@ rmsmp_status pack_host(const float* W, int64_t M, int64_t K, const uint8_t* sche
   }
   hp->blob.assign((size_t)off, 0);
 
-  // 4. fill tables and blob
+  // 4. fill tables and blob.  MFMA row i of a tile carries grouped offset tile_row_goff(i).
   for (int64_t t = 0; t < n_tiles; ++t) {
     const TileDesc& td = hp->tiles[(size_t)t];
-    for (int r = 0; r < td.nvalid; ++r) {
-      const int64_t p = t * TILE_M + r;
-      const int64_t g = td.g0 + r;
+    for (int i = 0; i < TILE_M; ++i) {
+      const int goff = tile_row_goff(i);
+      if (goff >= td.nvalid) continue;
+      const int64_t p = t * TILE_M + goff;
+      const int64_t g = td.g0 + goff;
       const int64_t orig = hp->perm[(size_t)g];
       hp->p_orig[(size_t)p] = (int32_t)orig;
       hp->p_gpos[(size_t)p] = (int32_t)g;
       hp->p_rowscale[(size_t)p] = hp->rowscale[(size_t)orig];
       hp->p_rowsum[(size_t)p] = hp->rowsum[(size_t)orig];
+      {
+        int32_t* m = &hp->p_meta[(size_t)p * 4];
+        std::memcpy(&m[0], &hp->rowscale[(size_t)orig], 4);
+        m[1] = hp->rowsum[(size_t)orig];
+        m[2] = (int32_t)orig;
+        m[3] = (int32_t)g;
+      }
       const bool pot = scheme[orig] == RMSMP_POT4;
       if (td.kind == TILE_NIB_LUT) {
         int8_t D[16];
@@ -287,12 +302,12 @@ rmsmp_status pack_host(const float* W, int64_t M, int64_t K, const uint8_t* sche
       }
       const int8_t* q = wint.data() + orig * K;
       for (int64_t ks = 0; ks < hp->nks; ++ks)
-        for (int kg = 0; kg < 4; ++kg) {
-          const int lane = kg * TILE_M + r;
+        for (int kb = 0; kb < 2; ++kb) {
+          const int lane = kb * TILE_M + i;
           int8_t v[16];
-          for (int i = 0; i < 16; ++i) {
-            const int64_t kk = ks * KSTEP + kg * 16 + i;
-            v[i] = kk < K ? q[hp->kmap[(size_t)kk]] : (int8_t)0;
+          for (int e = 0; e < 16; ++e) {
+            const int64_t kk = ks * KSTEP + kb * 16 + e;
+            v[e] = kk < K ? q[hp->kmap[(size_t)kk]] : (int8_t)0;
           }
           if (td.kind == TILE_I8) {
             uint8_t* dst = hp->blob.data() + td.blob_off + (ks * LANES + lane) * 16;
@@ -335,11 +350,13 @@ void unpack_host(const HostPacked& hp, const uint8_t* blob, int8_t* wint) {
   const int64_t K = hp.K;
   for (size_t t = 0; t < hp.tiles.size(); ++t) {
     const TileDesc& td = hp.tiles[t];
-    for (int r = 0; r < td.nvalid; ++r) {
-      const int64_t orig = hp.perm[(size_t)(td.g0 + r)];
+    for (int i = 0; i < TILE_M; ++i) {
+      const int goff = tile_row_goff(i);
+      if (goff >= td.nvalid) continue;
+      const int64_t orig = hp.perm[(size_t)(td.g0 + goff)];
       for (int64_t ks = 0; ks < hp.nks; ++ks)
-        for (int kg = 0; kg < 4; ++kg) {
-          const int lane = kg * TILE_M + r;
+        for (int kb = 0; kb < 2; ++kb) {
+          const int lane = kb * TILE_M + i;
           int8_t v[16];
           if (td.kind == TILE_I8) {
             const uint8_t* src = blob + td.blob_off + (ks * LANES + lane) * 16;
@@ -349,7 +366,7 @@ void unpack_host(const HostPacked& hp, const uint8_t* blob, int8_t* wint) {
             for (int b = 0; b < 8; ++b) {
               const uint8_t lo = src[b] & 0xf, hi = src[b] >> 4;
               if (td.kind == TILE_NIB_LUT) {
-                const uint32_t* T = &hp.p_lut[((size_t)t * TILE_M + r) * 4];
+                const uint32_t* T = &hp.p_lut[((size_t)t * TILE_M + goff) * 4];
                 v[2 * b] = lut_decode(T, lo);
                 v[2 * b + 1] = lut_decode(T, hi);
               } else {
@@ -358,9 +375,9 @@ void unpack_host(const HostPacked& hp, const uint8_t* blob, int8_t* wint) {
               }
             }
           }
-          for (int i = 0; i < 16; ++i) {
-            const int64_t kk = ks * KSTEP + kg * 16 + i;
-            if (kk < K) wint[orig * K + hp.kmap[(size_t)kk]] = v[i];
+          for (int e = 0; e < 16; ++e) {
+            const int64_t kk = ks * KSTEP + kb * 16 + e;
+            if (kk < K) wint[orig * K + hp.kmap[(size_t)kk]] = v[e];
           }
         }
     }

@@ -10,11 +10,18 @@
 
 namespace rmsmp {
 
-// A weight tile is TILE_M consecutive rows of one storage class; the K axis is cut in
-// steps of KSTEP elements, the depth of one v_mfma_i32_16x16x64_i8.
-constexpr int TILE_M = 16;
-constexpr int KSTEP = 64;
+// A weight tile is TILE_M rows of one storage class; the K axis is cut in steps of KSTEP
+// elements, the depth of one v_mfma_i32_32x32x32_i8 (the int8 MFMA shape that runs at the full
+// rate on gfx950; 16x16x64 runs at half of it).  K is padded to a multiple of KPAD_UNIT.
+constexpr int TILE_M = 32;
+constexpr int KSTEP = 32;
+constexpr int KPAD_UNIT = 64;
 constexpr int LANES = 64;
+
+// MFMA row i of a tile holds the row at grouped offset tile_row_goff(i): with this order the
+// 16 accumulator registers of a lane are 16 consecutive grouped rows (lanes 0..31 rows 0..15,
+// lanes 32..63 rows 16..31), so a lane can emit its 4-bit output codes as one 8-byte store.
+constexpr int tile_row_goff(int i) { return 16 * ((i / 4) % 2) + 4 * (i / 8) + i % 4; }
 
 // How a tile's codes are stored and decoded in registers.
 enum TileKind : int32_t {
@@ -46,10 +53,11 @@ struct HostPacked {
   std::vector<uint8_t> scheme;     // [M] original order
   std::vector<int32_t> kmap;       // [K] internal k -> original k
   std::vector<TileDesc> tiles;
-  // tables indexed by padded row p = tile*TILE_M + r
+  // tables indexed by padded grouped row p = tile*TILE_M + grouped offset
   std::vector<float> p_rowscale;
   std::vector<int32_t> p_rowsum, p_orig, p_gpos;
   std::vector<uint32_t> p_lut;     // 4 words per padded row
+  std::vector<int32_t> p_meta;     // 4 words per padded row: rowscale bits, rowsum, original row (-1 = padding), grouped position
   std::vector<uint8_t> blob;
 };
 
@@ -68,10 +76,7 @@ rmsmp_status assign_by_variance(const float* W, int64_t M, int64_t K, int64_t n_
 struct DevicePacked {
   const uint8_t* blob = nullptr;
   const TileDesc* tiles = nullptr;
-  const float* p_rowscale = nullptr;
-  const int32_t* p_rowsum = nullptr;
-  const int32_t* p_orig = nullptr;
-  const int32_t* p_gpos = nullptr;
+  const int32_t* p_meta = nullptr;  // per padded row: {rowscale bits, rowsum, original row or -1, grouped position}
   const uint32_t* p_lut = nullptr;
   int32_t n_tiles = 0;
   int32_t nks = 0;

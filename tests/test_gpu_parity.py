@@ -189,14 +189,59 @@ def run_conv(rm, oracle, geom, M, ratio, act_bits=4, z=0, relu=False, requant=Fa
 
 
 @pytest.mark.parametrize("geom", [(2, 64, 6, 6, 3, 3, 1, 1), (1, 128, 9, 7, 3, 3, 2, 1), (3, 64, 8, 8, 1, 1, 2, 0),
-                                  (2, 256, 5, 5, 3, 3, 1, 1)])
+                                  (2, 256, 5, 5, 3, 3, 1, 1), (2, 96, 5, 5, 3, 3, 1, 1), (1, 16, 9, 9, 5, 5, 2, 2),
+                                  (2, 32, 6, 5, 3, 3, 1, 2)])
 def test_conv_implicit_im2col(rm, oracle, geom):
     ws = run_conv(rm, oracle, geom, 48, (35, 60, 5), z=0, relu=True, requant=True)
     assert ws == 0
     run_conv(rm, oracle, geom, 34, (35, 60, 5), z=6, seed=1)
 
 
-@pytest.mark.parametrize("geom", [(2, 6, 9, 9, 3, 3, 1, 1), (1, 10, 8, 8, 5, 5, 2, 2), (2, 96, 5, 5, 3, 3, 1, 1)])
+@pytest.mark.parametrize("geom", [(5, 64, 14, 14, 3, 3, 1, 1), (2, 128, 10, 9, 3, 3, 1, 0), (3, 64, 7, 7, 1, 1, 1, 0),
+                                  (1, 64, 40, 40, 3, 3, 1, 1), (9, 128, 7, 7, 3, 3, 1, 1), (1, 64, 1, 1, 1, 1, 1, 0),
+                                  (2, 512, 7, 7, 3, 3, 1, 1)])
+@pytest.mark.parametrize("M", [48, 256, 90])
+def test_conv_stride1_lds_patch_kernel(rm, oracle, geom, M):
+    """Stride-1 layers with C % 64 == 0 take the LDS-resident patch kernel: several pixel tiles,
+    tiles that straddle images, a ragged last tile, no padding, 1x1, partial weight tiles."""
+    z = (sum(geom) + M) % 16
+    assert run_conv(rm, oracle, geom, M, (35, 60, 5), z=z, relu=True, requant=True, seed=3) == 0
+    run_conv(rm, oracle, geom, M, (100, 0, 0), z=0, seed=4)
+
+
+def test_config1_resnet_layer_full_size(rm, oracle):
+    """configs[1] at its benchmark size, every output compared: batch 32, 256->256, 14x14, 3x3 s1 p1
+    (GEMM 256 x 2304 x 6272), 60:35:5, ReLU + 4-bit requant."""
+    c = si.CONFIGS[1]
+    rng = si.rng_for(1)
+    M, C = c["M"], c["C"]
+    K = C * 9
+    Wt = si.weights_rowscaled(rng, M, K)
+    scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, *c["ratio"]))
+    x = si.act_codes_u4(rng, (c["B"], c["H"], c["W"], C))
+    p = rm.rmsmp_pack_weights(Wt, scheme, taps=9)
+    assert p.counts == (153, 90, 13)
+    d = rm.ConvDesc(c["B"], C, c["H"], c["W"], 3, 3, 1, 1)
+    od = oracle.conv_desc(c["B"], C, c["H"], c["W"], 3, 3, 1, 1)
+    N = c["B"] * c["H"] * c["W"]
+    ref = oracle.quantize_rows(Wt, scheme)
+    acc = oracle.conv_acc(ref["wint"].reshape(M, C, 3, 3), x.astype(np.int32), od, 0)
+    rs = oracle.rowsum(ref["wint"])
+    _, y, _ = oracle.epilogue(acc, rs, 0, ref["rowscale"], c["s_x"], None, True)
+    inv = np.float32(15.0 / float(np.percentile(y, 99.9)))
+    _, _, q = oracle.epilogue(acc, rs, 0, ref["rowscale"], c["s_x"], None, True, inv)
+    X = _to_dev(rm.pack_u4(x))
+    Yi = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    rm.rmsmp_conv2d(p, X, d, rm.make_epilogue(c["s_x"], 0, 4, None, False, rm.OUT_INT32), Yi)
+    Yq = torch.empty((N, M // 2), dtype=torch.uint8, device=DEV)
+    rm.rmsmp_conv2d(p, X, d, rm.make_epilogue(c["s_x"], 0, 4, None, True, rm.OUT_U4, inv), Yq)
+    torch.cuda.synchronize()
+    assert np.array_equal(Yi.cpu().numpy(), acc)
+    assert np.array_equal(grouped_codes(rm, Yq.cpu().numpy(), p.perm), q)
+    p.free()
+
+
+@pytest.mark.parametrize("geom", [(2, 6, 9, 9, 3, 3, 1, 1), (1, 10, 8, 8, 5, 5, 2, 2), (2, 24, 5, 5, 3, 3, 1, 1)])
 def test_conv_materialised_im2col_fallback(rm, oracle, geom):
     ws = run_conv(rm, oracle, geom, 40, (35, 60, 5), z=3, relu=True, requant=True)
     assert ws > 0

@@ -81,22 +81,28 @@ def test_pack_decides_boundaries_like_the_oracle(rm, oracle):
         assert np.array_equal(got["wint"].astype(np.int32), ref["wint"])
 
 
-def test_grouping_by_scheme_and_even_group_starts(rm, oracle):
+def test_grouping_by_scheme_in_whole_tiles(rm, oracle):
+    """Grouped order: Fixed-4 rows, then PoT-4, then Fixed-8.  A class whose size is not a multiple
+    of the 32-row tile hands its remainder to the next class, so every class starts on a tile
+    boundary (and in particular on an even row: two grouped rows share one 4-bit output byte)."""
     rng = np.random.default_rng(9)
-    for M, ratio in [(256, (35, 60, 5)), (64, (35, 60, 5)), (4096 // 8, (40, 50, 10)), (30, (50, 50, 0)),
-                     (22, (0, 95, 5)), (16, (100, 0, 0))]:
+    for M, ratio in [(256, (35, 60, 5)), (64, (35, 60, 5)), (512, (40, 50, 10)), (30, (50, 50, 0)),
+                     (22, (0, 95, 5)), (16, (100, 0, 0)), (96, (0, 100, 0)), (200, (65, 30, 5))]:
         W = si.weights_rowscaled(rng, M, 64)
         counts = oracle.ratio_counts(M, *ratio)
         scheme = si.scheme_permutation(rng, counts)
         got = rm.rmsmp_pack_roundtrip_host(W, scheme)
-        s = scheme[got["perm"]]
-        # grouped order: Fixed-4 rows first, then PoT-4, then Fixed-8, except that a class with an
-        # odd number of rows hands its last row to the next class so that every class starts at an
-        # even position (two grouped rows share one output byte)
-        order = {0: 0, 1: 1, 2: 2}
-        keys = [order[int(v)] for v in s]
-        n_out_of_order = sum(1 for a, b in zip(keys, keys[1:]) if a > b)
-        assert n_out_of_order <= 2
+        s = scheme[got["perm"]].astype(int)
+        n4, npot, n8 = counts
+        pure4 = n4 - n4 % 32 if (npot + n8) > 0 else n4
+        assert np.all(s[:pure4] == 0)
+        # PoT-4 rows never sit in the mask/shift class; Fixed-8 rows only in the last class
+        first_pot = np.nonzero(s == 1)[0].min() if npot else M
+        first_f8 = np.nonzero(s == 2)[0].min() if n8 else M
+        assert first_pot >= pure4 and first_f8 >= pure4
+        if n8:
+            i8_start = first_f8 - first_f8 % 32
+            assert np.all(s[:i8_start] != 2)
         assert np.bincount(scheme, minlength=3).tolist() == list(counts)
 
 
