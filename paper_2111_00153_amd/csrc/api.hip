@@ -108,6 +108,10 @@ rmsmp_status rmsmp_pack_weights(const float* W, int64_t M, int64_t K, const uint
   p->dev.p_lut = (const uint32_t*)put(h.p_lut.data(), h.p_lut.size() * 4, n_lut);
   p->dev.n_tiles = (int32_t)h.tiles.size();
   p->dev.nks = (int32_t)h.nks;
+  for (const auto& t : h.tiles) {
+    p->dev.class_tiles[t.kind] += 1;
+    p->dev.class_rows[t.kind] += t.nvalid;
+  }
   if (e != hipSuccess) {
     (void)hipFree(p->dev_alloc);
     delete p;

@@ -16,6 +16,20 @@ namespace rmsmp {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
+// Optional per-wave phase timestamps for tuning builds (-DRMSMP_PHASE_TIMING); compiled out otherwise.
+#ifdef RMSMP_PHASE_TIMING
+__device__ unsigned long long* g_phase_buf = nullptr;
+#define RMSMP_PHASE(id)                                                                          \
+  do {                                                                                           \
+    if (g_phase_buf && (threadIdx.x & 63) == 0)                                                  \
+      g_phase_buf[((blockIdx.y * gridDim.x + blockIdx.x) * 8 + (threadIdx.x >> 6)) * 16 + (id)] = clock64(); \
+  } while (0)
+#else
+#define RMSMP_PHASE(id) \
+  do {                  \
+  } while (0)
+#endif
+
 // ---------------------------------------------------------------- operand decode
 
 // Eight two's-complement nibbles per word -> int8 = 16*q, in MFMA slot order.
@@ -77,6 +91,11 @@ template <int KIND>
 __device__ __forceinline__ typename RawFrag<KIND>::type load_raw(const uint8_t* lane_ptr, int64_t step_bytes_index) {
   return *(const typename RawFrag<KIND>::type*)(lane_ptr + step_bytes_index);
 }
+// same, from a wave-uniform base and a 32-bit per-lane byte offset
+template <int KIND>
+__device__ __forceinline__ typename RawFrag<KIND>::type load_raw(const uint8_t* uniform_base, uint32_t lane_off) {
+  return *(const typename RawFrag<KIND>::type*)(uniform_base + lane_off);
+}
 
 template <int KIND>
 __device__ __forceinline__ v4i decode_raw(typename RawFrag<KIND>::type w, uint4 T);
@@ -93,6 +112,32 @@ __device__ __forceinline__ v4i decode_raw<TILE_I8>(uint4 w, uint4) {
   return (v4i){(int)w.x, (int)w.y, (int)w.z, (int)w.w};
 }
 
+// ---------------------------------------------------------------- tile lookup
+
+// Class, live rows and blob offset of weight tile mt, from the class sizes alone (no memory access).
+__device__ __forceinline__ TileRef tile_ref(const DevicePacked& w, int mt) {
+  const int64_t nib_tile = (int64_t)w.nks * LANES * 8, i8_tile = (int64_t)w.nks * LANES * 16;
+  const int t0 = w.class_tiles[0], t1 = w.class_tiles[1];
+  TileRef t;
+  int idx;
+  if (mt < t0) {
+    t.kind = TILE_NIB_SHIFT;
+    idx = mt;
+    t.blob_off = (int64_t)mt * nib_tile;
+  } else if (mt < t0 + t1) {
+    t.kind = TILE_NIB_LUT;
+    idx = mt - t0;
+    t.blob_off = (int64_t)mt * nib_tile;
+  } else {
+    t.kind = TILE_I8;
+    idx = mt - t0 - t1;
+    t.blob_off = (int64_t)(t0 + t1) * nib_tile + (int64_t)idx * i8_tile;
+  }
+  const int left = w.class_rows[t.kind] - idx * TILE_M;
+  t.nvalid = left < TILE_M ? left : TILE_M;
+  return t;
+}
+
 // ---------------------------------------------------------------- epilogue
 
 // Every fp32 operation is rounded on its own so that codes are reproducible bit for bit.
@@ -104,64 +149,136 @@ __device__ __forceinline__ float dequant(int a, float m, bool has_bias, float b,
 }
 
 __device__ __forceinline__ uint32_t requant_u4(float y, float inv_s) {
-  float t = rintf(__fmul_rn(y, inv_s));
-  t = fminf(fmaxf(t, 0.0f), 15.0f);
+  // clamp(rint(y/s), 0, 15); the median of {t, 0, 15} is that clamp in one instruction
+  const float t = __builtin_amdgcn_fmed3f(rintf(__fmul_rn(y, inv_s)), 0.0f, 15.0f);
   return (uint32_t)t;
 }
 
-// Row metadata of the 16 grouped rows a lane finishes: {rowscale bits, rowsum, original row, grouped position}.
-struct RowMeta {
-  int4 m[16];
+// What the epilogue needs from the kernel arguments.  Kernel arguments are fetched with scalar
+// loads where they are first used; at the end of a kernel that is a cold miss in front of the
+// stores, so kernels copy these fields at their start and pin them in registers.
+struct EpArgs {
+  void* Y;
+  const float* bias;
+  int64_t N, M;
+  float act_scale, out_inv_scale;
+  int zp, relu, out_kind;
 };
 
-__device__ __forceinline__ void load_row_meta(const GemmArgs& a, int mt, int lane, RowMeta& rm) {
-  const int4* src = (const int4*)a.w.p_meta + (int64_t)mt * TILE_M + 16 * (lane >> 5);
+__device__ __forceinline__ EpArgs pin_epilogue_args(const GemmArgs& a) {
+  EpArgs e;
+  e.Y = a.Y;
+  e.bias = a.ep.bias;
+  e.N = a.N;
+  e.M = a.M;
+  e.act_scale = a.ep.act_scale;
+  e.out_inv_scale = a.ep.out_inv_scale;
+  e.zp = a.ep.act_zero_point;
+  e.relu = a.ep.relu;
+  e.out_kind = a.ep.out_kind;
+  // an empty asm that "modifies" the values keeps the loads here
+  asm volatile("" : "+s"(e.Y), "+s"(e.bias), "+s"(e.N), "+s"(e.M), "+s"(e.act_scale), "+s"(e.out_inv_scale), "+s"(e.zp),
+               "+s"(e.relu), "+s"(e.out_kind));
+  return e;
+}
+
+// Row metadata of the 16 consecutive grouped rows a lane finishes.
+struct RowMeta {
+  int4 m[16];  // {rowscale bits, rowsum, original row (-1 = padding), grouped position}
+};
+
+__device__ __forceinline__ void load_row_meta(const DevicePacked& w, int mt, int lane, RowMeta& rm) {
+  const int4* src = (const int4*)w.p_meta + (int64_t)mt * TILE_M + 16 * (lane >> 5);
 #pragma unroll
   for (int r = 0; r < 16; ++r) rm.m[r] = src[r];
 }
 
-// Finish one 32x32 accumulator tile: zero-point correction, per-row scale, bias, ReLU, then
-// int32 / fp32 / nibble-packed 4-bit store.  Register r of lane l is grouped row 16*(l/32)+r of
-// the weight tile and column n; the 16 registers of a lane are 16 consecutive grouped rows.
-__device__ __forceinline__ void finish_tile(const GemmArgs& a, int kind, const v16i& acc, const RowMeta& rm,
-                                            int64_t n) {
-  if (n >= a.N) return;
-  const int zp = a.ep.act_zero_point;
-  const bool has_bias = a.ep.bias != nullptr;
-  const bool relu = a.ep.relu != 0;
-  const int out_kind = a.ep.out_kind;
-  uint32_t packed[2] = {0u, 0u};
-  int n_rows = 0;
+// Finish NB 32x32 accumulator tiles of the same weight tile (NB pixel blocks): zero-point
+// correction, per-row scale, bias, ReLU, then int32 / fp32 / nibble-packed 4-bit store.
+// Register r of lane l is grouped row 16*(l/32)+r of the weight tile and column n[j]; the 16
+// registers of a lane are 16 consecutive grouped rows.  n_rows = how many of the lane's 16 rows
+// exist (live rows of a tile are a prefix).  Straight-line code: padding rows are computed and
+// dropped at the store, and all results are formed before the first store is issued (a store
+// pins its data registers until it has left, so interleaving would stall on every block).
+template <int NB>
+__device__ __forceinline__ void finish_tiles(const EpArgs& a, int kind, const v16i (&acc)[NB], const RowMeta& rm,
+                                             int n_rows, const int64_t (&n)[NB]) {
+  if (n_rows <= 0) return;
+  const int zp = a.zp;
+  const bool has_bias = a.bias != nullptr;
+  const bool relu = a.relu != 0;
+  const int out_kind = a.out_kind;
+  int v[NB][16];
+#pragma unroll
+  for (int j = 0; j < NB; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) v[j][r] = kind == TILE_NIB_SHIFT ? acc[j][r] >> 4 : acc[j][r];
+  if (zp != 0) {
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) v[j][r] -= zp * rm.m[r].y;
+  }
+  if (out_kind == 0) {
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (r < n_rows && n[j] < a.N) ((int32_t*)a.Y)[(int64_t)rm.m[r].z * a.N + n[j]] = v[j][r];
+    return;
+  }
+  float bias[16], m[16];
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    const int orig = rm.m[r].z;
-    if (orig < 0) continue;
-    ++n_rows;
-    int v = acc[r];
-    if (kind == TILE_NIB_SHIFT) v >>= 4;
-    v -= zp * rm.m[r].y;
-    if (out_kind == 0) {
-      ((int32_t*)a.Y)[(int64_t)orig * a.N + n] = v;
-    } else {
-      const float m = __fmul_rn(__int_as_float(rm.m[r].x), a.ep.act_scale);
-      const float y = dequant(v, m, has_bias, has_bias ? a.ep.bias[orig] : 0.0f, relu);
-      if (out_kind == 1) {
-        ((float*)a.Y)[(int64_t)orig * a.N + n] = y;
-      } else {
-        packed[r >> 3] |= requant_u4(y, a.ep.out_inv_scale) << (4 * (r & 7));
-      }
-    }
+    bias[r] = 0.0f;
+    m[r] = __fmul_rn(__int_as_float(rm.m[r].x), a.act_scale);
   }
-  if (out_kind == 2 && n_rows > 0) {
-    // valid rows of a tile are a prefix, so they start at register 0 and the first grouped
-    // position is a multiple of 16
-    uint8_t* dst = (uint8_t*)a.Y + n * (a.M / 2) + (rm.m[0].w >> 1);
+  if (has_bias) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) bias[r] = a.bias[rm.m[r].z < 0 ? 0 : rm.m[r].z];
+  }
+  if (out_kind == 1) {
+    float y[NB][16];
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) y[j][r] = dequant(v[j][r], m[r], has_bias, bias[r], relu);
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (r < n_rows && n[j] < a.N) ((float*)a.Y)[(int64_t)rm.m[r].z * a.N + n[j]] = y[j][r];
+    return;
+  }
+  RMSMP_PHASE(12);
+  uint32_t packed[NB][2];
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    packed[j][0] = packed[j][1] = 0u;
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      packed[j][r >> 3] |= requant_u4(dequant(v[j][r], m[r], has_bias, bias[r], relu), a.out_inv_scale) << (4 * (r & 7));
+  }
+  RMSMP_PHASE(13);
+#ifdef RMSMP_TUNE_NO_STORE
+  if (packed[0][0] != 0x12345679u) return;
+#endif
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    if (n[j] >= a.N) continue;
+    // the first grouped position of a lane is a multiple of 16
+    uint8_t* dst = (uint8_t*)a.Y + n[j] * (a.M / 2) + (rm.m[0].w >> 1);
     if (n_rows == 16 && (((uintptr_t)dst) & 7) == 0) {
-      *(uint2*)dst = make_uint2(packed[0], packed[1]);
+      *(uint2*)dst = make_uint2(packed[j][0], packed[j][1]);
     } else {
-      for (int b = 0; b < n_rows / 2; ++b) dst[b] = (uint8_t)(packed[b >> 2] >> (8 * (b & 3)));
+      for (int b = 0; b < n_rows / 2; ++b) dst[b] = (uint8_t)(packed[j][b >> 2] >> (8 * (b & 3)));
     }
   }
+}
+
+__device__ __forceinline__ int lane_rows(int nvalid, int lane) {
+  const int left = nvalid - 16 * (lane >> 5);
+  return left < 0 ? 0 : left > 16 ? 16 : left;
 }
 
 // ---------------------------------------------------------------- general tile kernel
@@ -176,9 +293,8 @@ constexpr int GEN_BK = 64;      // K elements staged per step
 constexpr int GEN_STRIDE = 80;  // bytes per column in LDS (64 + 16 pad)
 
 template <int KIND>
-__device__ __forceinline__ void general_slab_mfma(const uint8_t* lane_ptr, int s, uint4 T, const uint8_t* sB, int lane,
-                                                  v16i (&acc)[2], typename RawFrag<KIND>::type w0,
-                                                  typename RawFrag<KIND>::type w1) {
+__device__ __forceinline__ void general_slab_mfma(uint4 T, const uint8_t* sB, int lane, v16i (&acc)[2],
+                                                  typename RawFrag<KIND>::type w0, typename RawFrag<KIND>::type w1) {
   const v4i av0 = decode_raw<KIND>(w0, T);
   const v4i av1 = decode_raw<KIND>(w1, T);
   const int c = lane & 31, kb = lane >> 5;
@@ -194,6 +310,7 @@ __device__ __forceinline__ void general_slab_mfma(const uint8_t* lane_ptr, int s
 template <int ACT_BITS, bool CONV, bool VEC>
 __global__ __launch_bounds__(256) void gemm_general_kernel(GemmArgs a) {
   __shared__ __attribute__((aligned(16))) uint8_t sB[GEN_BN * GEN_STRIDE];
+  const EpArgs ea = pin_epilogue_args(a);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -222,17 +339,13 @@ __global__ __launch_bounds__(256) void gemm_general_kernel(GemmArgs a) {
   // ---- weight tile role
   const int mt = blockIdx.y * 4 + wave;
   const bool wave_on = mt < a.w.n_tiles;
-  int kind = TILE_NIB_SHIFT;
-  int64_t blob_off = 0;
-  if (wave_on) {
-    kind = __builtin_amdgcn_readfirstlane(a.w.tiles[mt].kind);
-    blob_off = a.w.tiles[mt].blob_off;
-  }
+  const TileRef tr = tile_ref(a.w, wave_on ? mt : 0);
+  const int kind = tr.kind;
   uint4 T = make_uint4(0, 0, 0, 0);
   if (wave_on && kind == TILE_NIB_LUT)
     T = *(const uint4*)(a.w.p_lut + ((int64_t)mt * TILE_M + tile_row_goff(lane & 31)) * 4);
   const int frag_bytes = kind == TILE_I8 ? 16 : 8;
-  const uint8_t* lane_ptr = a.w.blob + blob_off + (int64_t)lane * frag_bytes;
+  const uint8_t* lane_ptr = a.w.blob + tr.blob_off + (int64_t)lane * frag_bytes;
   const int64_t step_bytes = (int64_t)LANES * frag_bytes;
 
   v16i acc[2];
@@ -306,21 +419,20 @@ __global__ __launch_bounds__(256) void gemm_general_kernel(GemmArgs a) {
     __syncthreads();
     if (wave_on) {
       if (kind == TILE_NIB_SHIFT)
-        general_slab_mfma<TILE_NIB_SHIFT>(lane_ptr, s, T, sB, lane, acc, make_uint2(raw0.x, raw0.y),
-                                          make_uint2(raw1.x, raw1.y));
+        general_slab_mfma<TILE_NIB_SHIFT>(T, sB, lane, acc, make_uint2(raw0.x, raw0.y), make_uint2(raw1.x, raw1.y));
       else if (kind == TILE_NIB_LUT)
-        general_slab_mfma<TILE_NIB_LUT>(lane_ptr, s, T, sB, lane, acc, make_uint2(raw0.x, raw0.y),
-                                        make_uint2(raw1.x, raw1.y));
+        general_slab_mfma<TILE_NIB_LUT>(T, sB, lane, acc, make_uint2(raw0.x, raw0.y), make_uint2(raw1.x, raw1.y));
       else
-        general_slab_mfma<TILE_I8>(lane_ptr, s, T, sB, lane, acc, raw0, raw1);
+        general_slab_mfma<TILE_I8>(T, sB, lane, acc, raw0, raw1);
     }
   }
 
   if (!wave_on) return;
   RowMeta rm;
-  load_row_meta(a, mt, lane, rm);
-#pragma unroll
-  for (int j = 0; j < 2; ++j) finish_tile(a, kind, acc[j], rm, n0 + 32 * j + (lane & 31));
+  load_row_meta(a.w, mt, lane, rm);
+  const int n_rows = lane_rows(tr.nvalid, lane);
+  const int64_t ncol[2] = {n0 + (lane & 31), n0 + 32 + (lane & 31)};
+  finish_tiles<2>(ea, kind, acc, rm, n_rows, ncol);
 }
 
 template <int ACT_BITS, bool CONV, bool VEC>
@@ -336,201 +448,327 @@ static int launch_general(const GemmArgs& a, hipStream_t s) {
 // (two weight tiles) x 128 output pixels.  The pixels it needs -- a contiguous run of the
 // flattened NHWC input -- are read from memory once, decoded to int8 and kept in LDS for all
 // KH*KW taps; out-of-image taps point at a row filled with the zero-point code.  The patch is
-// shared by both weight tiles whatever their class.  Eight waves: each pair of waves owns one
-// weight tile x 64 pixels and splits the K steps between them (even / odd), so that one wave's
-// decode and LDS reads run under the other's MFMAs (a wave cannot overlap its own); the two
-// partial sums are added through LDS at the end (int32 addition is exact in any order).
-// Packed weights stream from global memory straight into a register ring that runs PT_RING K
-// steps ahead of the MFMAs; everything is unrolled so that the ring is addressed statically.
+// shared by both weight tiles whatever their class.
+//
+// Four waves, one per SIMD.  A wave owns a 64-row x 64-pixel block (two weight fragments from
+// registers, two activation fragments from LDS, four MFMAs per K step, so each LDS byte and
+// each weight byte feeds two MFMAs) and every other K step; the two partial sums of a block are
+// added through LDS at the end (int32 addition is exact in any order).  The decode and address
+// arithmetic of a step are independent of its MFMAs and issue in their shadow.
+//
+// The two tiles of a work-group are tile y and tile (n_tiles-1-y): tiles are sorted by class,
+// so a table-decoded (PoT) tile, whose decode is the most expensive, is paired with a cheap one
+// whenever the layer has both, and no work-group is left with two expensive tiles.
+//
+// Packed weights stream from global memory straight into a register ring that runs PT_RING
+// steps ahead of the MFMAs.  A kernel starts with cold caches, so every global read that does
+// not depend on another is issued up front (ring, row metadata, the whole patch): one memory
+// latency is paid.  The K loop is fully unrolled straight-line code: with branches in it the
+// compiler can no longer count outstanding loads and waits for all of them at every step, and a
+// rolled loop makes it copy the ring registers at the back edge, which drains the ring as well.
 constexpr int PT_BN = 128;
+constexpr int PT_THREADS = 256;
+constexpr int PT_PATCH_UNROLL = 6;              // 16-byte patch pieces in flight per thread
+constexpr int PT_META_BYTES = 2 * TILE_M * 16;  // row metadata of the work-group's 64 rows, kept at the start of LDS
+constexpr int PT_RING = 8;                      // K steps of packed weights in flight per wave and tile
+constexpr int PT_KSPLIT = 2;                    // waves sharing one output block
 
-template <int KIND, int TAPS, int CPT>
-__device__ __forceinline__ void patch_mainloop(const uint8_t* lane_ptr, uint4 T, const uint8_t* smem,
-                                               const int (&row_addr)[2], const uint32_t (&vmask)[2], int zaddr,
-                                               int tap_row_bytes, int tap_col_bytes, v16i (&acc)[2]) {
-  constexpr int OWN_PER_TAP = CPT / 2;
-  constexpr int NOWN = TAPS * OWN_PER_TAP;
-  constexpr int FRAG = KIND == TILE_I8 ? 16 : 8;
-  constexpr int RING = NOWN < (KIND == TILE_I8 ? 12 : 18) ? NOWN : (KIND == TILE_I8 ? 12 : 18);
-  constexpr int64_t OWN_STRIDE = 2 * LANES * FRAG;  // this wave takes every other K step
-  typename RawFrag<KIND>::type ring[RING];
-#pragma unroll
-  for (int u = 0; u < RING; ++u) ring[u] = load_raw<KIND>(lane_ptr, u * OWN_STRIDE);
-  // LDS address of this lane's B fragment for every tap and both pixel blocks
-  constexpr int KW3 = TAPS == 9 ? 3 : 1;
-  int addr[TAPS][2];
-#pragma unroll
-  for (int t = 0; t < TAPS; ++t) {
-    const int toff = (t / KW3) * tap_row_bytes + (t % KW3) * tap_col_bytes;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) addr[t][j] = ((vmask[j] >> t) & 1u) ? row_addr[j] + toff : zaddr;
-  }
-  // B fragments are read one step ahead of the MFMAs that use them
-  v4i b0 = *(const v4i*)(smem + addr[0][0]);
-  v4i b1 = *(const v4i*)(smem + addr[0][1]);
-#pragma unroll
-  for (int s = 0; s < NOWN; ++s) {
-    const v4i av = decode_raw<KIND>(ring[s % RING], T);
-    if (s + RING < NOWN) ring[s % RING] = load_raw<KIND>(lane_ptr, (int64_t)(s + RING) * OWN_STRIDE);
-    v4i nb0 = b0, nb1 = b1;
-    if (s + 1 < NOWN) {
-      const int t1 = (s + 1) / OWN_PER_TAP, u1 = (s + 1) % OWN_PER_TAP;
-      nb0 = *(const v4i*)(smem + addr[t1][0] + u1 * 2 * KSTEP);
-      nb1 = *(const v4i*)(smem + addr[t1][1] + u1 * 2 * KSTEP);
-    }
-    acc[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, b0, acc[0], 0, 0, 0);
-    acc[1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, b1, acc[1], 0, 0, 0);
-    b0 = nb0;
-    b1 = nb1;
-    // keep each step's prefetch where it is: without this the scheduler sinks the loads next
-    // to their use and the ring degenerates to one or two loads in flight
-    __builtin_amdgcn_sched_barrier(0);
-  }
+struct PatchGeom {
+  int row_stride;     // LDS bytes per patch pixel (C + 16)
+  int patch_rows;     // pixels staged per work-group
+  uint32_t magic_hw;  // ceil(2^32 / (OH*OW)), 0 when OH*OW == 1
+  uint32_t magic_ow;  // ceil(2^32 / OW), 0 when OW == 1
+};
+
+// n / d for n*d < 2^32 with magic = ceil(2^32/d) (0 stands for d == 1): one multiply.
+__device__ __forceinline__ int fast_div(int n, uint32_t magic) {
+  return magic ? (int)__umulhi((uint32_t)n, magic) : n;
 }
 
-template <int TAPS, int CPT>
-__global__ __launch_bounds__(512) void conv_patch_kernel(GemmArgs a, int row_stride, int patch_rows) {
-  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+// KIND0 / KIND1: storage classes of the work-group's two weight tiles (template parameters so
+// that the K loop has no branches).
+template <int TAPS, int CPT, int KIND0, int KIND1>
+__device__ __forceinline__ void patch_body(const GemmArgs& a, const PatchGeom& g, uint8_t* smem_raw, int mt0, int mt1,
+                                           const TileRef& tr0, const TileRef& tr1, bool two) {
+  constexpr int C = CPT * KSTEP;
+  constexpr int KW = TAPS == 9 ? 3 : 1;
+  constexpr int KH = KW;
+  constexpr int NKS = TAPS * CPT;
+  constexpr int NSTEP = NKS / PT_KSPLIT;  // K steps per wave (CPT is even)
+  constexpr int SPT = CPT / PT_KSPLIT;    // of which per tap
+  static_assert(CPT % PT_KSPLIT == 0, "a tap must hold a whole number of K steps per wave");
+  RMSMP_PHASE(0);
+  const EpArgs ea = pin_epilogue_args(a);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int pair = wave & 3;     // which (weight tile, 64-pixel half)
-  const int parity = wave >> 2;  // which K steps
-  const int mi = pair >> 1, nh = pair & 1;
-  const int64_t n0 = (int64_t)blockIdx.x * PT_BN;
-  constexpr int C = CPT * KSTEP;
-  constexpr int KW = TAPS == 9 ? 3 : 1;
+  const int wt = wave & 1;   // which 64-pixel half of the work-group's 128 pixels
+  const int kq = wave >> 1;  // K steps kq, kq+2, ...
+  const int n0 = blockIdx.x * PT_BN;
   const int H = a.d.H, W = a.d.W, pad = a.d.pad;
   const int hw_out = a.OH * a.OW;
-
-  // ---- weight tile of this wave pair; start its stream and the row metadata right away
-  const int mt = blockIdx.y * 2 + mi;
-  const bool wave_on = mt < a.w.n_tiles;
-  int kind = TILE_NIB_SHIFT;
-  int64_t blob_off = 0;
-  if (wave_on) {
-    kind = __builtin_amdgcn_readfirstlane(a.w.tiles[mt].kind);
-    blob_off = a.w.tiles[mt].blob_off;
-  }
-  uint4 T = make_uint4(0, 0, 0, 0);
-  if (wave_on && kind == TILE_NIB_LUT)
-    T = *(const uint4*)(a.w.p_lut + ((int64_t)mt * TILE_M + tile_row_goff(lane & 31)) * 4);
-  const int frag_bytes = kind == TILE_I8 ? 16 : 8;
-  const uint8_t* lane_ptr = a.w.blob + blob_off + ((int64_t)parity * LANES + lane) * frag_bytes;
+  const int row_stride = g.row_stride, patch_rows = g.patch_rows;
 
   // flattened input index of tap (0,0) for output pixel n (may be negative / out of image)
-  auto base_index = [&](int64_t n, int& b, int& oh, int& ow) -> int64_t {
-    b = (int)(n / hw_out);
-    const int rem = (int)(n - (int64_t)b * hw_out);
-    oh = rem / a.OW;
+  auto base_index = [&](int n, int& oh, int& ow) -> int {
+    const int b = fast_div(n, g.magic_hw);
+    const int rem = n - b * hw_out;
+    oh = fast_div(rem, g.magic_ow);
     ow = rem - oh * a.OW;
-    return ((int64_t)b * H + (oh - pad)) * W + (ow - pad);
+    return (b * H + (oh - pad)) * W + (ow - pad);
   };
-  int tb, toh, tow;
-  int64_t f_lo = base_index(n0, tb, toh, tow);
+  int toh, tow;
+  int f_lo = base_index(n0, toh, tow);
   if (f_lo < 0) f_lo = 0;
-  const int64_t total_px = (int64_t)a.d.B * H * W;
 
-  // ---- stage the patch: pixels f_lo .. f_lo+patch_rows-1, decoded to int8, row_stride bytes each.
-  // Loads are issued in batches of PATCH_UNROLL before the first use so that they overlap.
-  {
-    const uint8_t* X = (const uint8_t*)a.X;
-    constexpr int CHUNKS = C / 16;  // 16-channel chunks per pixel
-    constexpr int PATCH_UNROLL = 6;
-    const int total = patch_rows * CHUNKS;
-    for (int base = 0; base < total; base += 512 * PATCH_UNROLL) {
-      uint2 w[PATCH_UNROLL];
+  // ---- 1. the patch loads go out first: the main loop cannot start before the patch has been
+  // decoded into LDS.  Pixels f_lo .. f_lo+patch_rows-1 are one contiguous byte range of X;
+  // piece idx (32 channels, 16 bytes) sits at byte 16*idx of it and goes, decoded to int8, to LDS
+  // byte 32*idx + 16*(idx / pieces-per-pixel) (rows are padded by 16 bytes).  Reads past the end
+  // of X are clamped (those rows are never used).
+  const uint8_t* X = (const uint8_t*)a.X;
+  constexpr int PIECES = C / 32;
+  const int total = patch_rows * PIECES;
+  const int64_t x_bytes = (int64_t)a.d.B * H * W * (C / 2);
+  const int64_t src0 = (int64_t)f_lo * (C / 2);
+  uint4 pw[PT_PATCH_UNROLL];
 #pragma unroll
-      for (int u = 0; u < PATCH_UNROLL; ++u) {
-        const int idx = base + u * 512 + tid;
-        const int px = idx / CHUNKS, ch = idx % CHUNKS;
-        const int64_t f = f_lo + px;
-        w[u] = make_uint2(0, 0);
-        if (idx < total && f < total_px) w[u] = *(const uint2*)(X + f * (C / 2) + ch * 8);
-      }
-#pragma unroll
-      for (int u = 0; u < PATCH_UNROLL; ++u) {
-        const int idx = base + u * 512 + tid;
-        const int px = idx / CHUNKS, ch = idx % CHUNKS;
-        if (idx < total) *(v4i*)(smem + px * row_stride + ch * 16) = decode_act_u4(w[u]);
-      }
-    }
-    // the zero-point row
-    const uint32_t zf = 0x01010101u * (uint32_t)(a.ep.act_zero_point & 15);
-    if (tid < CHUNKS) *(v4i*)(smem + patch_rows * row_stride + tid * 16) = (v4i){(int)zf, (int)zf, (int)zf, (int)zf};
+  for (int u = 0; u < PT_PATCH_UNROLL; ++u) {
+    int64_t off = src0 + (int64_t)(u * PT_THREADS + tid) * 16;
+    off = off < x_bytes - 16 ? off : x_bytes - 16;
+    pw[u] = *(const uint4*)(X + off);
   }
 
-  // ---- per-lane LDS address of tap (0,0) and validity mask over the taps, for both pixel blocks
-  const int lane_off = 16 * (lane >> 5) + parity * KSTEP;
+  // ---- 2. weight rings of the two tiles, lookup tables, row metadata
+  constexpr int fb0 = KIND0 == TILE_I8 ? 16 : 8, fb1 = KIND1 == TILE_I8 ? 16 : 8;
+  constexpr int step0 = LANES * fb0, step1 = LANES * fb1;  // bytes per K step
+  // uniform base of this wave's first K step + 32-bit lane offset; stepping through K is scalar work
+  const uint8_t* const wb0 = a.w.blob + tr0.blob_off + kq * step0;
+  const uint8_t* const wb1 = a.w.blob + tr1.blob_off + kq * step1;
+  const uint32_t wl0 = (uint32_t)lane * fb0, wl1 = (uint32_t)lane * fb1;
+  typename RawFrag<KIND0>::type ring0[PT_RING];
+  typename RawFrag<KIND1>::type ring1[PT_RING];
+#pragma unroll
+  for (int u = 0; u < PT_RING; ++u) {
+    if (u < NSTEP) {
+      ring0[u] = load_raw<KIND0>(wb0 + (int64_t)u * PT_KSPLIT * step0, wl0);
+      ring1[u] = load_raw<KIND1>(wb1 + (int64_t)u * PT_KSPLIT * step1, wl1);
+    }
+  }
+  uint4 T0 = make_uint4(0, 0, 0, 0), T1 = T0;
+  if (KIND0 == TILE_NIB_LUT) T0 = *(const uint4*)(a.w.p_lut + ((int64_t)mt0 * TILE_M + tile_row_goff(lane & 31)) * 4);
+  if (KIND1 == TILE_NIB_LUT) T1 = *(const uint4*)(a.w.p_lut + ((int64_t)mt1 * TILE_M + tile_row_goff(lane & 31)) * 4);
+  // row metadata: threads 0..31 fetch tile 0's rows, 32..63 tile 1's; parked in LDS until the end
+  int4 meta_row = make_int4(0, 0, -1, -1);
+  if (tid < 2 * TILE_M) meta_row = ((const int4*)a.w.p_meta)[(tid < TILE_M ? mt0 : mt1) * TILE_M + (tid & (TILE_M - 1))];
+  uint8_t* const smem_meta = smem_raw;
+  uint8_t* const smem = smem_raw + PT_META_BYTES;  // the patch, later the exchange buffer
+  RMSMP_PHASE(8);
+
+  // decode the patch pieces into LDS; a patch larger than one batch takes more rounds
+  {
+    auto put_piece = [&](int idx, uint4 w) {
+      uint8_t* dst = smem + idx * 32 + (idx / PIECES) * 16;
+      *(v4i*)dst = decode_act_u4(make_uint2(w.x, w.y));
+      *(v4i*)(dst + 16) = decode_act_u4(make_uint2(w.z, w.w));
+    };
+    RMSMP_PHASE(7);
+#pragma unroll
+    for (int u = 0; u < PT_PATCH_UNROLL; ++u) {
+      const int idx = u * PT_THREADS + tid;
+      if (idx < total) put_piece(idx, pw[u]);
+    }
+#pragma unroll 1
+    for (int base = PT_THREADS * PT_PATCH_UNROLL; base < total; base += PT_THREADS) {
+      const int idx = base + tid;
+      int64_t off = src0 + (int64_t)idx * 16;
+      off = off < x_bytes - 16 ? off : x_bytes - 16;
+      const uint4 w = *(const uint4*)(X + off);
+      if (idx < total) put_piece(idx, w);
+    }
+    // a constant row behind the patch: the zero-point code, for out-of-image taps
+    const uint32_t zf = 0x01010101u * (uint32_t)(a.ep.act_zero_point & 15);
+    if (tid < C / 16) *(v4i*)(smem + patch_rows * row_stride + tid * 16) = (v4i){(int)zf, (int)zf, (int)zf, (int)zf};
+    if (tid < 2 * TILE_M) *(int4*)(smem_meta + tid * 16) = meta_row;
+  }
+  RMSMP_PHASE(11);
+
+  // ---- 3. per lane and 32-pixel block: LDS address of tap (0,0) and the taps inside the image.
+  // Validity is separable: tap (kh,kw) is inside iff kh is in [kh_lo,kh_hi] and kw in [kw_lo,kw_hi].
+  const int lane_off = 16 * (lane >> 5) + kq * KSTEP;
   const int zaddr = patch_rows * row_stride + lane_off;
   int row_addr[2];
   uint32_t vmask[2];
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    const int64_t n = n0 + 64 * nh + 32 * j + (lane & 31);
-    int b = 0, oh = 0, ow = 0;
-    int64_t f0 = 0;
-    const bool n_ok = n < a.N;
-    if (n_ok) f0 = base_index(n, b, oh, ow);
+    const int n = n0 + 64 * wt + 32 * j + (lane & 31);
+    const bool n_ok = n < (int)a.N;
+    int oh = 0, ow = 0;
+    const int f0 = base_index(n_ok ? n : n0, oh, ow);
+    const int kw_lo = max(0, pad - ow), kw_hi = min(KW - 1, W - 1 + pad - ow);
+    const int kh_lo = max(0, pad - oh), kh_hi = min(KH - 1, H - 1 + pad - oh);
+    const uint32_t wbits = kw_hi >= kw_lo ? ((2u << kw_hi) - (1u << kw_lo)) : 0u;  // bits kw_lo..kw_hi
     uint32_t m = 0;
 #pragma unroll
-    for (int t = 0; t < TAPS; ++t) {
-      const int kh = t / KW, kw = t % KW;
-      const int ih = oh - pad + kh, iw = ow - pad + kw;
-      if (n_ok && ih >= 0 && ih < H && iw >= 0 && iw < W) m |= 1u << t;
-    }
-    vmask[j] = m;
-    row_addr[j] = (int)(f0 - f_lo) * row_stride + lane_off;
+    for (int kh = 0; kh < KH; ++kh) m |= (kh >= kh_lo && kh <= kh_hi) ? wbits << (KW * kh) : 0u;
+    vmask[j] = n_ok ? m : 0u;
+    row_addr[j] = (f0 - f_lo) * row_stride + lane_off;
   }
+  // LDS address of this lane's B fragment of pixel block j at tap t.  The tap of a step is known
+  // at compile time (the same for both waves of a block); steps inside a tap differ by an
+  // immediate offset and the per-wave part kq*KSTEP sits in the lane offsets.
+  const int tap_row_bytes = W * row_stride;
+  auto tap_base = [&](int t, int j) -> int {
+    const int kh = t / KW, kw = t - kh * KW;
+    return ((vmask[j] >> t) & 1u) ? row_addr[j] + kh * tap_row_bytes + kw * row_stride : zaddr;
+  };
 
-  RowMeta rm;
-  if (wave_on) load_row_meta(a, mt, lane, rm);
-
-  v16i acc[2];
-  for (int j = 0; j < 2; ++j)
-    for (int r = 0; r < 16; ++r) acc[j][r] = 0;
-
+  RMSMP_PHASE(1);
   __syncthreads();  // patch is in LDS
+  RMSMP_PHASE(2);
 
-  if (wave_on) {
-    if (kind == TILE_NIB_SHIFT)
-      patch_mainloop<TILE_NIB_SHIFT, TAPS, CPT>(lane_ptr, T, smem, row_addr, vmask, zaddr, W * row_stride, row_stride, acc);
-    else if (kind == TILE_NIB_LUT)
-      patch_mainloop<TILE_NIB_LUT, TAPS, CPT>(lane_ptr, T, smem, row_addr, vmask, zaddr, W * row_stride, row_stride, acc);
-    else
-      patch_mainloop<TILE_I8, TAPS, CPT>(lane_ptr, T, smem, row_addr, vmask, zaddr, W * row_stride, row_stride, acc);
+  // ---- 4. main loop over this wave's K steps; B fragments are fetched one step ahead
+  v16i acc[2][2];  // [weight tile][pixel block]
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+  {
+    int cur0 = tap_base(0, 0), cur1 = tap_base(0, 1);
+    v4i b0 = *(const v4i*)(smem + cur0);
+    v4i b1 = *(const v4i*)(smem + cur1);
+    // Software pipeline: step i multiplies with fragments decoded during step i-1 and decodes
+    // those of step i+1, so the decode has no MFMA waiting for it.  A wave issues in order and
+    // the matrix pipe takes one MFMA every 32 cycles, so four MFMAs in a row would block the
+    // wave for 96 cycles; the scheduling groups below ask for the step's vector instructions to
+    // be spread between its MFMAs instead, where they issue for free.
+    v4i av0 = decode_raw<KIND0>(ring0[0], T0);
+    v4i av1 = decode_raw<KIND1>(ring1[0], T1);
+    if (PT_RING < NSTEP) {
+      ring0[0] = load_raw<KIND0>(wb0 + (int64_t)PT_RING * PT_KSPLIT * step0, wl0);
+      ring1[0] = load_raw<KIND1>(wb1 + (int64_t)PT_RING * PT_KSPLIT * step1, wl1);
+    }
+    constexpr int NV0 = KIND0 == TILE_NIB_SHIFT ? 6 : KIND0 == TILE_NIB_LUT ? 22 : 0;
+    constexpr int NV1 = KIND1 == TILE_NIB_SHIFT ? 6 : KIND1 == TILE_NIB_LUT ? 22 : 0;
+    constexpr int NVQ = (NV0 + NV1 + 4 + 3) / 4;  // vector instructions per MFMA slot
+    // step i of this wave (K step 2*i + kq); everything indexed by i is static after unrolling
+    auto step = [&](int i) {
+      v4i nav0 = av0, nav1 = av1, nb0 = b0, nb1 = b1;
+      if (i + 1 < NSTEP) {
+        const int u = (i + 1) % PT_RING;
+        nav0 = decode_raw<KIND0>(ring0[u], T0);
+        nav1 = decode_raw<KIND1>(ring1[u], T1);
+        if (i + 1 + PT_RING < NSTEP) {
+          ring0[u] = load_raw<KIND0>(wb0 + (int64_t)(i + 1 + PT_RING) * PT_KSPLIT * step0, wl0);
+          ring1[u] = load_raw<KIND1>(wb1 + (int64_t)(i + 1 + PT_RING) * PT_KSPLIT * step1, wl1);
+        }
+        if ((i + 1) % SPT == 0) {
+          cur0 = tap_base((i + 1) / SPT, 0);
+          cur1 = tap_base((i + 1) / SPT, 1);
+        }
+        nb0 = *(const v4i*)(smem + cur0 + ((i + 1) % SPT) * PT_KSPLIT * KSTEP);
+        nb1 = *(const v4i*)(smem + cur1 + ((i + 1) % SPT) * PT_KSPLIT * KSTEP);
+      }
+      acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av1, b1, acc[1][1], 0, 0, 0);
+      av0 = nav0;
+      av1 = nav1;
+      b0 = nb0;
+      b1 = nb1;
+      // desired issue order of this step: MFMA, a quarter of the vector work, MFMA, ...
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);    // the two LDS reads of the next B fragments
+      __builtin_amdgcn_sched_group_barrier(0x002, NVQ, 0);  // VALU
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, NVQ, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);    // the two ring loads
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, NVQ, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, NVQ, 0);
+      // and nothing crosses into the next step: without this the scheduler also sinks the ring
+      // loads next to their use and the ring degenerates to one or two loads in flight
+      __builtin_amdgcn_sched_barrier(0);
+    };
+#pragma unroll
+    for (int i = 0; i < NSTEP; ++i) step(i);
   }
 
-  // ---- add the two partial sums of a pair: each wave hands over the block it does not finish
+  RMSMP_PHASE(3);
+  // ---- 5. add the two partial sums of a block.  Wave kq finishes weight tile kq of the block
+  // (both pixel blocks) and hands the other tile's partial sums to its partner.
   __syncthreads();  // everyone is done with the patch; LDS is reused for the exchange
+  RMSMP_PHASE(4);
   {
-    int* xch = (int*)smem + wave * (16 * LANES);
+    int* dst = (int*)smem + wave * (2 * 16 * LANES);  // slot [giver wave][pixel block]
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      v4i give;
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) give[e] = parity ? acc[0][4 * q + e] : acc[1][4 * q + e];
-      *(v4i*)(xch + q * (4 * LANES) + lane * 4) = give;
-    }
+      for (int q = 0; q < 4; ++q) {
+        v4i give;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) give[e] = kq ? acc[0][j][4 * q + e] : acc[1][j][4 * q + e];
+        *(v4i*)(dst + j * (16 * LANES) + q * (4 * LANES) + lane * 4) = give;
+      }
   }
   __syncthreads();
-  if (!wave_on) return;
+  if (kq == 1 && !two) return;
+  v16i mine[2];
   {
-    const int partner = wave ^ 4;
-    const int* xch = (const int*)smem + partner * (16 * LANES);
-    v16i mine;
+    const int* src = (const int*)smem + (wave ^ 2) * (2 * 16 * LANES);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const v4i got = *(const v4i*)(xch + q * (4 * LANES) + lane * 4);
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) mine[4 * q + e] = (parity ? acc[1][4 * q + e] : acc[0][4 * q + e]) + got[e];
-    }
-    finish_tile(a, kind, mine, rm, n0 + 64 * nh + 32 * parity + (lane & 31));
+      for (int q = 0; q < 4; ++q) {
+        const v4i got = *(const v4i*)(src + j * (16 * LANES) + q * (4 * LANES) + lane * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mine[j][4 * q + e] = (kq ? acc[1][j][4 * q + e] : acc[0][j][4 * q + e]) + got[e];
+      }
   }
+  RMSMP_PHASE(5);
+  RowMeta rm;
+  {
+    const int4* src = (const int4*)smem_meta + kq * TILE_M + 16 * (lane >> 5);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) rm.m[r] = src[r];
+  }
+  const int n_rows = lane_rows(kq ? tr1.nvalid : tr0.nvalid, lane);
+  const int kind = kq ? KIND1 : KIND0;
+  const int64_t ncol[2] = {(int64_t)n0 + 64 * wt + (lane & 31), (int64_t)n0 + 64 * wt + 32 + (lane & 31)};
+  finish_tiles<2>(ea, kind, mine, rm, n_rows, ncol);
+  RMSMP_PHASE(6);
 }
 
+template <int TAPS, int CPT>
+__global__ __launch_bounds__(PT_THREADS) void conv_patch_kernel(GemmArgs a, PatchGeom g) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+  // tiles y and n_tiles-1-y; the middle tile of an odd count stands alone (its second tile
+  // shadows it and is never stored)
+  const int mt0 = blockIdx.y;
+  const int mt1 = a.w.n_tiles - 1 - mt0;
+  const bool two = mt1 > mt0;
+  const TileRef tr0 = tile_ref(a.w, mt0);
+  const TileRef tr1 = tile_ref(a.w, mt1);
+  // tiles are sorted by class, so kind0 <= kind1
+#define RMSMP_BODY(K0, K1) \
+  if (tr0.kind == K0 && tr1.kind == K1) return patch_body<TAPS, CPT, K0, K1>(a, g, smem_raw, mt0, mt1, tr0, tr1, two);
+  RMSMP_BODY(TILE_NIB_SHIFT, TILE_NIB_SHIFT)
+  RMSMP_BODY(TILE_NIB_SHIFT, TILE_NIB_LUT)
+  RMSMP_BODY(TILE_NIB_SHIFT, TILE_I8)
+  RMSMP_BODY(TILE_NIB_LUT, TILE_NIB_LUT)
+  RMSMP_BODY(TILE_NIB_LUT, TILE_I8)
+  RMSMP_BODY(TILE_I8, TILE_I8)
+#undef RMSMP_BODY
+}
+
+static uint32_t div_magic(int64_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + (uint64_t)d - 1) / (uint64_t)d); }
+
 // Geometry checks for the LDS-resident kernel; fills the LDS layout when it applies.
-static bool patch_kernel_applies(const GemmArgs& a, int* row_stride, int* patch_rows, size_t* lds_bytes) {
+static bool patch_kernel_applies(const GemmArgs& a, PatchGeom* g, size_t* lds_bytes) {
   if (!a.conv || a.ep.act_bits != 4 || a.d.stride != 1) return false;
   const int taps = a.d.KH * a.d.KW;
   if (!(taps == 1 || (a.d.KH == 3 && a.d.KW == 3))) return false;
@@ -541,19 +779,25 @@ static bool patch_kernel_applies(const GemmArgs& a, int* row_stride, int* patch_
   const int64_t span = (int64_t)PT_BN + (int64_t)(a.d.KH - 1) * a.d.W + (a.d.KW - 1)
                        + (int64_t)(a.d.H - a.OH) * a.d.W * ((PT_BN + a.OH * a.OW - 1) / (a.OH * a.OW) + 1)
                        + (int64_t)(a.d.W - a.OW) * ((PT_BN + a.OW - 1) / a.OW + 1);
+  // 32-bit pixel arithmetic and exact one-multiply division in the kernel
+  const int64_t hw = (int64_t)a.OH * a.OW, in_px = (int64_t)a.d.B * a.d.H * a.d.W;
+  if ((a.N + PT_BN) * hw >= ((int64_t)1 << 32) || in_px * (a.d.C / 2) >= ((int64_t)1 << 40)) return false;
+  if (in_px + span >= ((int64_t)1 << 31) / (a.d.C + 16)) return false;
   const int rs = a.d.C + 16;
-  const size_t need = (size_t)(span + 1) * rs;
-  const size_t xch = 8 * 16 * LANES * 4;
+  const size_t need = (size_t)(span + 1) * rs;  // patch + zero-point row
+  const size_t xch = (size_t)4 * 2 * 16 * LANES * 4;
   if (need > 150 * 1024) return false;
-  *row_stride = rs;
-  *patch_rows = (int)span;
-  *lds_bytes = need > xch ? need : xch;
+  g->row_stride = rs;
+  g->patch_rows = (int)span;
+  g->magic_hw = div_magic(hw);
+  g->magic_ow = div_magic(a.OW);
+  *lds_bytes = PT_META_BYTES + (need > xch ? need : xch);
   return true;
 }
 
 // Dynamic LDS above 64 KiB must be allowed per kernel once (per device); remember what was set.
 template <int TAPS, int CPT>
-static int launch_patch_t(const GemmArgs& a, int row_stride, int patch_rows, size_t lds, dim3 grid, hipStream_t s) {
+static int launch_patch_t(const GemmArgs& a, PatchGeom g, size_t lds, dim3 grid, hipStream_t s) {
   static bool allowed[64] = {false};
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
@@ -565,16 +809,16 @@ static int launch_patch_t(const GemmArgs& a, int row_stride, int patch_rows, siz
     if (e != hipSuccess) return (int)e;
     allowed[dev] = true;
   }
-  hipLaunchKernelGGL((conv_patch_kernel<TAPS, CPT>), grid, dim3(512), lds, s, a, row_stride, patch_rows);
+  hipLaunchKernelGGL((conv_patch_kernel<TAPS, CPT>), grid, dim3(PT_THREADS), lds, s, a, g);
   return (int)hipGetLastError();
 }
 
-static int launch_patch(const GemmArgs& a, int row_stride, int patch_rows, size_t lds, hipStream_t s) {
+static int launch_patch(const GemmArgs& a, PatchGeom g, size_t lds, hipStream_t s) {
   dim3 grid((unsigned)((a.N + PT_BN - 1) / PT_BN), (unsigned)((a.w.n_tiles + 1) / 2), 1);
   const int taps = a.d.KH * a.d.KW;
   const int cpt = a.d.C / KSTEP;
 #define RMSMP_PATCH_CASE(TP, CP) \
-  if (taps == TP && cpt == CP) return launch_patch_t<TP, CP>(a, row_stride, patch_rows, lds, grid, s);
+  if (taps == TP && cpt == CP) return launch_patch_t<TP, CP>(a, g, lds, grid, s);
   RMSMP_PATCH_CASE(9, 2)
   RMSMP_PATCH_CASE(9, 4)
   RMSMP_PATCH_CASE(9, 8)
@@ -591,9 +835,9 @@ int launch_gemm(const GemmArgs& a, void* stream) {
   hipStream_t s = (hipStream_t)stream;
   if (a.N <= 0) return 0;
   if (a.conv) {
-    int rs, pr;
+    PatchGeom g;
     size_t lds;
-    if (patch_kernel_applies(a, &rs, &pr, &lds)) return launch_patch(a, rs, pr, lds, s);
+    if (patch_kernel_applies(a, &g, &lds)) return launch_patch(a, g, lds, s);
     return a.ep.act_bits == 4 ? launch_general<4, true, true>(a, s) : launch_general<8, true, true>(a, s);
   }
   const bool vec = (a.K % 16) == 0;

@@ -80,6 +80,18 @@ struct DevicePacked {
   const uint32_t* p_lut = nullptr;
   int32_t n_tiles = 0;
   int32_t nks = 0;
+  // Tiles are ordered by class (TileKind 0, 1, 2) and all tiles of a class have the same size,
+  // so a kernel finds a tile's class, blob offset and live row count from these six numbers
+  // without touching memory.
+  int32_t class_tiles[3] = {0, 0, 0};
+  int32_t class_rows[3] = {0, 0, 0};
+};
+
+// Where weight tile mt lives, computed from DevicePacked alone.
+struct TileRef {
+  int kind;
+  int nvalid;
+  int64_t blob_off;
 };
 
 struct GemmArgs {
