@@ -19,6 +19,10 @@ sys.path.insert(0, ROOT)
 
 INT8_MFMA_PEAK_TOPS = 5000.0  # MI355X dense int8, published
 HBM_PEAK_GBS = 8000.0
+# HBM-side bytes per launch of the timed kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a
+# 256 MiB device copy (profiles/conv_patch_kernel_configs1.md); a counter reading cannot be taken from
+# inside this script, so the last measured value is carried here.
+MEASURED_TRAFFIC_BYTES = 8550516
 
 
 def make_conv_workload(cfg_id=1):
@@ -59,6 +63,9 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (a known-size kernel to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE readings with)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); the path shards over output "
@@ -136,10 +143,16 @@ def main():
                                "fused ReLU + uint4 requant",
                    "rows_per_scheme": list(wl["counts"])},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
-                     "kernel": "conv_patch_kernel<9>", "avg_launch_us": round(kern_ms * 1e3, 3)},
+                     "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES,
+                     "kernel": "rmsmp::conv_patch_kernel<9, 8>", "avg_launch_us": round(kern_ms * 1e3, 3)},
         "cpu_baseline": base,
     }
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
     print(json.dumps(out))
     p.free()
 
