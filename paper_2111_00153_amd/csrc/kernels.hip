@@ -831,6 +831,155 @@ static int launch_patch(const GemmArgs& a, PatchGeom g, size_t lds, hipStream_t 
   return (int)hipErrorInvalidValue;
 }
 
+// ---------------------------------------------------------------- skinny GEMM (N <= 64)
+//
+// A handful of activation columns against a large weight matrix moves every packed weight byte
+// once and does almost no arithmetic: the kernel is a weight stream at memory speed.  One
+// work-group per weight tile, eight waves; wave w takes one eighth of K.  It issues all of its
+// weight reads (one fully coalesced 512-byte / 1-KiB fragment per K step) before touching any of
+// them, so a work-group keeps its whole 32-row slab in flight; its slice of the activations goes
+// through a private LDS region (packed, decoded per fragment).  The eight partial sums are added
+// through LDS and finished by the usual epilogue.
+constexpr int SK_THREADS = 512;
+constexpr int SK_WAVES = 8;
+constexpr int SK_CHUNK = 16;  // K steps whose loads are in flight together per wave
+
+template <int KIND, int NB>
+__device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, const TileRef& tr, int mt) {
+  const EpArgs ea = pin_epilogue_args(a);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  constexpr int FRAG = KIND == TILE_I8 ? 16 : 8;
+  constexpr int ROWS = 32 * NB;
+  const int nks = a.w.nks;
+  const int S = (nks + SK_WAVES - 1) / SK_WAVES;  // K steps per wave
+  const int ks0 = wave * S;
+  const uint8_t* wbase = a.w.blob + tr.blob_off;
+  const uint32_t wl = (uint32_t)lane * FRAG;
+  uint4 T = make_uint4(0, 0, 0, 0);
+  if (KIND == TILE_NIB_LUT) T = *(const uint4*)(a.w.p_lut + ((int64_t)mt * TILE_M + tile_row_goff(lane & 31)) * 4);
+  const uint8_t* X = (const uint8_t*)a.X;
+  const int64_t ldx = a.K / 2;
+  const int x_stride = SK_CHUNK * 16 + 8;  // LDS bytes per activation row of a chunk (padded)
+  uint8_t* xs = smem + wave * (ROWS * x_stride);
+
+  v16i acc[NB];
+#pragma unroll
+  for (int j = 0; j < NB; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0;
+
+#pragma unroll 1
+  for (int c0 = 0; c0 < S; c0 += SK_CHUNK) {
+    // all weight fragments of the chunk first ...
+    typename RawFrag<KIND>::type raw[SK_CHUNK];
+#pragma unroll
+    for (int u = 0; u < SK_CHUNK; ++u) {
+      int ks = ks0 + c0 + u;
+      ks = ks < nks ? ks : nks - 1;
+      raw[u] = load_raw<KIND>(wbase + (int64_t)ks * (LANES * FRAG), wl);
+    }
+    // ... then this wave's slice of the activations: ROWS rows x (SK_CHUNK*16) packed bytes
+    {
+      const int64_t col0 = (int64_t)(ks0 + c0) * 16;  // byte offset inside an activation row
+#pragma unroll
+      for (int i = 0; i < ROWS * SK_CHUNK / LANES; ++i) {
+        const int pidx = i * LANES + lane;
+        const int row = pidx / SK_CHUNK, piece = pidx % SK_CHUNK;
+        const int64_t n = row < (int)a.N ? row : (int)a.N - 1;  // rows past N repeat the last one; never stored
+        int64_t cb = col0 + piece * 16;
+        cb = cb + 16 <= ldx ? cb : ldx - 16;  // past the end of K: any data, its weights are zero
+        const uint4 w = *(const uint4*)(X + n * ldx + cb);
+        *(uint2*)(xs + row * x_stride + piece * 16) = make_uint2(w.x, w.y);
+        *(uint2*)(xs + row * x_stride + piece * 16 + 8) = make_uint2(w.z, w.w);
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave's LDS writes have landed (region is private)
+#pragma unroll
+    for (int u = 0; u < SK_CHUNK; ++u) {
+      const int ks = ks0 + c0 + u;
+      if (c0 + u < S && ks < nks) {
+        const v4i av = decode_raw<KIND>(raw[u], T);
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          const uint2 xw = *(const uint2*)(xs + (32 * j + (lane & 31)) * x_stride + u * 16 + (lane >> 5) * 8);
+          acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, decode_act_u4(xw), acc[j], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // ---- add the eight partial sums: wave j (< NB) finishes pixel block j
+  __syncthreads();
+  {
+    int* dst = (int*)smem + wave * (NB * 16 * LANES);
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *(v4i*)(dst + j * (16 * LANES) + q * (4 * LANES) + lane * 4) =
+            (v4i){acc[j][4 * q], acc[j][4 * q + 1], acc[j][4 * q + 2], acc[j][4 * q + 3]};
+  }
+  __syncthreads();
+  if (wave >= NB) return;
+  v16i sum[1];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) sum[0][r] = 0;
+#pragma unroll 1
+  for (int w = 0; w < SK_WAVES; ++w) {
+    const int* src = (const int*)smem + w * (NB * 16 * LANES) + wave * (16 * LANES);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const v4i got = *(const v4i*)(src + q * (4 * LANES) + lane * 4);
+      sum[0][4 * q] += got.x;
+      sum[0][4 * q + 1] += got.y;
+      sum[0][4 * q + 2] += got.z;
+      sum[0][4 * q + 3] += got.w;
+    }
+  }
+  RowMeta rm;
+  load_row_meta(a.w, mt, lane, rm);
+  const int64_t ncol[1] = {32 * wave + (lane & 31)};
+  finish_tiles<1>(ea, KIND, sum, rm, lane_rows(tr.nvalid, lane), ncol);
+}
+
+template <int NB>
+__global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(GemmArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+  const int mt = blockIdx.x;
+  const TileRef tr = tile_ref(a.w, mt);
+  if (tr.kind == TILE_NIB_SHIFT)
+    skinny_body<TILE_NIB_SHIFT, NB>(a, smem_raw, tr, mt);
+  else if (tr.kind == TILE_NIB_LUT)
+    skinny_body<TILE_NIB_LUT, NB>(a, smem_raw, tr, mt);
+  else
+    skinny_body<TILE_I8, NB>(a, smem_raw, tr, mt);
+}
+
+static bool skinny_applies(const GemmArgs& a) {
+  return !a.conv && a.ep.act_bits == 4 && a.N <= 64 && a.K % 64 == 0 && a.K >= 512;
+}
+
+template <int NB>
+static int launch_skinny_t(const GemmArgs& a, hipStream_t s) {
+  const size_t xs = (size_t)SK_WAVES * 32 * NB * (SK_CHUNK * 16 + 8);
+  const size_t xch = (size_t)SK_WAVES * NB * 16 * LANES * 4;
+  const size_t lds = xs > xch ? xs : xch;
+  static bool allowed[64] = {false};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= 64) return (int)hipErrorInvalidDevice;
+  if (!allowed[dev]) {
+    e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<NB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return (int)e;
+    allowed[dev] = true;
+  }
+  hipLaunchKernelGGL(gemm_skinny_kernel<NB>, dim3((unsigned)a.w.n_tiles), dim3(SK_THREADS), lds, s, a);
+  return (int)hipGetLastError();
+}
+
 int launch_gemm(const GemmArgs& a, void* stream) {
   hipStream_t s = (hipStream_t)stream;
   if (a.N <= 0) return 0;
@@ -840,6 +989,7 @@ int launch_gemm(const GemmArgs& a, void* stream) {
     if (patch_kernel_applies(a, &g, &lds)) return launch_patch(a, g, lds, s);
     return a.ep.act_bits == 4 ? launch_general<4, true, true>(a, s) : launch_general<8, true, true>(a, s);
   }
+  if (skinny_applies(a)) return a.N <= 32 ? launch_skinny_t<1>(a, s) : launch_skinny_t<2>(a, s);
   const bool vec = (a.K % 16) == 0;
   if (a.ep.act_bits == 4) return vec ? launch_general<4, false, true>(a, s) : launch_general<4, false, false>(a, s);
   return vec ? launch_general<8, false, true>(a, s) : launch_general<8, false, false>(a, s);
