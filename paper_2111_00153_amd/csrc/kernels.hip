@@ -16,17 +16,34 @@ namespace rmsmp {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-// Optional per-wave phase timestamps for tuning builds (-DRMSMP_PHASE_TIMING); compiled out otherwise.
+// Optional per-wave phase timestamps for tuning builds (-DRMSMP_PHASE_TIMING); compiled out
+// otherwise.  A stamp is one clock read parked in the first KiB of dynamic LDS (16 slots per
+// wave); the kernel copies the slots to g_phase_buf when it ends, so a stamp costs no memory
+// round trip where it is taken.
 #ifdef RMSMP_PHASE_TIMING
 __device__ unsigned long long* g_phase_buf = nullptr;
-#define RMSMP_PHASE(id)                                                                          \
-  do {                                                                                           \
-    if (g_phase_buf && (threadIdx.x & 63) == 0)                                                  \
-      g_phase_buf[((blockIdx.y * gridDim.x + blockIdx.x) * 8 + (threadIdx.x >> 6)) * 16 + (id)] = clock64(); \
+constexpr int PHASE_LDS_BYTES = 1024;
+extern __shared__ __attribute__((aligned(16))) uint8_t phase_smem[];
+#define RMSMP_PHASE(id)                                                                                  \
+  do {                                                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                                   \
+    if ((threadIdx.x & 63) == 0) ((unsigned long long*)phase_smem)[(threadIdx.x >> 6) * 16 + (id)] = clock64(); \
+    __builtin_amdgcn_sched_barrier(0);                                                                   \
+  } while (0)
+#define RMSMP_PHASE_FLUSH()                                                                              \
+  do {                                                                                                   \
+    if (g_phase_buf && (threadIdx.x & 63) == 0)                                                          \
+      for (int i_ = 0; i_ < 16; ++i_)                                                                    \
+        g_phase_buf[((blockIdx.y * gridDim.x + blockIdx.x) * 8 + (threadIdx.x >> 6)) * 16 + i_] =        \
+            ((unsigned long long*)phase_smem)[(threadIdx.x >> 6) * 16 + i_];                             \
   } while (0)
 #else
+constexpr int PHASE_LDS_BYTES = 0;
 #define RMSMP_PHASE(id) \
   do {                  \
+  } while (0)
+#define RMSMP_PHASE_FLUSH() \
+  do {                      \
   } while (0)
 #endif
 
@@ -141,28 +158,26 @@ __device__ __forceinline__ TileRef tile_ref(const DevicePacked& w, int mt) {
 // ---------------------------------------------------------------- epilogue
 
 // Every fp32 operation is rounded on its own so that codes are reproducible bit for bit.
-__device__ __forceinline__ float dequant(int a, float m, bool has_bias, float b, bool relu) {
-  float y = __fmul_rn((float)a, m);
-  if (has_bias) y = __fadd_rn(y, b);
-  if (relu) y = fmaxf(y, 0.0f);
-  return y;
-}
-
-__device__ __forceinline__ uint32_t requant_u4(float y, float inv_s) {
-  // clamp(rint(y/s), 0, 15); the median of {t, 0, 15} is that clamp in one instruction
-  const float t = __builtin_amdgcn_fmed3f(rintf(__fmul_rn(y, inv_s)), 0.0f, 15.0f);
-  return (uint32_t)t;
-}
-
 // What the epilogue needs from the kernel arguments.  Kernel arguments are fetched with scalar
 // loads where they are first used; at the end of a kernel that is a cold miss in front of the
 // stores, so kernels copy these fields at their start and pin them in registers.
+// The epilogue's pointers pass through an empty asm (see pin_epilogue_args), which hides from the
+// compiler that they point to global memory; without the explicit address space it would emit
+// flat loads and stores, whose completion it cannot count and therefore waits for in full.
+#define RMSMP_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ RMSMP_GLOBAL T* as_global(T* p) {
+  return (RMSMP_GLOBAL T*)p;
+}
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+
 struct EpArgs {
   void* Y;
   const float* bias;
   int64_t N, M;
   float act_scale, out_inv_scale;
   int zp, relu, out_kind;
+  bool stamps = false;  // tuning builds: this kernel reserved the stamp slots in LDS
 };
 
 __device__ __forceinline__ EpArgs pin_epilogue_args(const GemmArgs& a) {
@@ -182,15 +197,57 @@ __device__ __forceinline__ EpArgs pin_epilogue_args(const GemmArgs& a) {
   return e;
 }
 
-// Row metadata of the 16 consecutive grouped rows a lane finishes.
+// Row metadata of the 16 consecutive grouped rows a lane finishes, held in registers:
+// {rowscale bits, rowsum, original row (-1 = padding), grouped position} per row.
 struct RowMeta {
-  int4 m[16];  // {rowscale bits, rowsum, original row (-1 = padding), grouped position}
+  int4 m[16];
+  __device__ __forceinline__ int scale_bits(int r) const { return m[r].x; }
+  __device__ __forceinline__ int rowsum(int r) const { return m[r].y; }
+  __device__ __forceinline__ int orig(int r) const { return m[r].z; }
+  __device__ __forceinline__ int gpos0() const { return m[0].w; }
+};
+
+// The same, read on demand from a table in LDS laid out field by field (rows x 4 fields): an
+// epilogue then only touches the fields its output kind needs and keeps few of them in registers.
+struct RowMetaLds {
+  const int* base;  // LDS: field f of the lane's row r at base[f * rows + r]
+  int rows;
+  __device__ __forceinline__ int scale_bits(int r) const { return base[r]; }
+  __device__ __forceinline__ int rowsum(int r) const { return base[rows + r]; }
+  __device__ __forceinline__ int orig(int r) const { return base[2 * rows + r]; }
+  __device__ __forceinline__ int gpos0() const { return base[3 * rows]; }
 };
 
 __device__ __forceinline__ void load_row_meta(const DevicePacked& w, int mt, int lane, RowMeta& rm) {
   const int4* src = (const int4*)w.p_meta + (int64_t)mt * TILE_M + 16 * (lane >> 5);
 #pragma unroll
   for (int r = 0; r < 16; ++r) rm.m[r] = src[r];
+}
+
+// 4-bit output codes of one pixel block: clamp(rint(y * inv_s), 0, 15) for the lane's 16 rows,
+// row r in nibble r of the 64-bit result.  BIAS / RELU say which of the optional steps exist, so
+// that the common cases carry no dead instructions.  The float-to-byte conversion packs a value
+// that is already an exact integer in [0, 15], so its own rounding mode plays no role.
+template <bool BIAS, bool RELU>
+__device__ __forceinline__ void requant_block(const v16i& v, const float (&m)[16], const float (&bias)[16], float inv_s,
+                                              uint32_t (&packed)[2]) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    uint32_t even = 0u, odd = 0u;  // bytes: rows 8h + {0,2,4,6} and 8h + {1,3,5,7}
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = 8 * h + i;
+      float y = __fmul_rn((float)v[r], m[r]);
+      if (BIAS) y = __fadd_rn(y, bias[r]);
+      if (RELU) y = fmaxf(y, 0.0f);
+      const float t = __builtin_amdgcn_fmed3f(rintf(__fmul_rn(y, inv_s)), 0.0f, 15.0f);
+      if (i & 1)
+        odd = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, odd);
+      else
+        even = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, even);
+    }
+    packed[h] = even | (odd << 4);
+  }
 }
 
 // Finish NB 32x32 accumulator tiles of the same weight tile (NB pixel blocks): zero-point
@@ -200,80 +257,102 @@ __device__ __forceinline__ void load_row_meta(const DevicePacked& w, int mt, int
 // exist (live rows of a tile are a prefix).  Straight-line code: padding rows are computed and
 // dropped at the store, and all results are formed before the first store is issued (a store
 // pins its data registers until it has left, so interleaving would stall on every block).
-template <int NB>
-__device__ __forceinline__ void finish_tiles(const EpArgs& a, int kind, const v16i (&acc)[NB], const RowMeta& rm,
+//
+// Accumulators of shift-decoded tiles are 16 times the true sums.  The integer output divides
+// them (an exact shift); the float paths fold the factor into the per-row multiplier instead:
+// float(16 a) * (m / 16) and float(a) * m are the same float, because scaling by a power of two
+// commutes with rounding.
+template <int NB, class Meta>
+__device__ __forceinline__ void finish_tiles(const EpArgs& a, int kind, const v16i (&acc)[NB], const Meta& rm,
                                              int n_rows, const int64_t (&n)[NB]) {
   if (n_rows <= 0) return;
   const int zp = a.zp;
   const bool has_bias = a.bias != nullptr;
   const bool relu = a.relu != 0;
   const int out_kind = a.out_kind;
-  int v[NB][16];
+  const bool x16 = kind == TILE_NIB_SHIFT;
+  v16i v[NB];
 #pragma unroll
-  for (int j = 0; j < NB; ++j)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) v[j][r] = kind == TILE_NIB_SHIFT ? acc[j][r] >> 4 : acc[j][r];
-  if (zp != 0) {
-#pragma unroll
-    for (int j = 0; j < NB; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) v[j][r] -= zp * rm.m[r].y;
-  }
+  for (int j = 0; j < NB; ++j) v[j] = acc[j];
   if (out_kind == 0) {
 #pragma unroll
     for (int j = 0; j < NB; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        if (r < n_rows && n[j] < a.N) ((int32_t*)a.Y)[(int64_t)rm.m[r].z * a.N + n[j]] = v[j][r];
+      for (int r = 0; r < 16; ++r) {
+        const int s = (x16 ? v[j][r] >> 4 : v[j][r]) - zp * rm.rowsum(r);
+        if (r < n_rows && n[j] < a.N) as_global((int32_t*)a.Y)[(int64_t)rm.orig(r) * a.N + n[j]] = s;
+      }
     return;
   }
+  if (zp != 0) {
+    const int zs = x16 ? 16 * zp : zp;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int c = zs * rm.rowsum(r);
+#pragma unroll
+      for (int j = 0; j < NB; ++j) v[j][r] -= c;
+    }
+  }
+  if (a.stamps) RMSMP_PHASE(8);
   float bias[16], m[16];
+  const float fold = x16 ? 0.0625f : 1.0f;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     bias[r] = 0.0f;
-    m[r] = __fmul_rn(__int_as_float(rm.m[r].x), a.act_scale);
+    m[r] = __fmul_rn(__fmul_rn(__int_as_float(rm.scale_bits(r)), a.act_scale), fold);
   }
   if (has_bias) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) bias[r] = a.bias[rm.m[r].z < 0 ? 0 : rm.m[r].z];
+    for (int r = 0; r < 16; ++r) bias[r] = as_global(a.bias)[rm.orig(r) < 0 ? 0 : rm.orig(r)];
   }
   if (out_kind == 1) {
+    // adding a zero bias and taking the maximum with -inf change nothing, so one code path serves
+    // every combination of the two options
+    const float floor_y = relu ? 0.0f : -__builtin_inff();
     float y[NB][16];
 #pragma unroll
     for (int j = 0; j < NB; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) y[j][r] = dequant(v[j][r], m[r], has_bias, bias[r], relu);
+      for (int r = 0; r < 16; ++r) y[j][r] = fmaxf(__fadd_rn(__fmul_rn((float)v[j][r], m[r]), bias[r]), floor_y);
 #pragma unroll
     for (int j = 0; j < NB; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r)
-        if (r < n_rows && n[j] < a.N) ((float*)a.Y)[(int64_t)rm.m[r].z * a.N + n[j]] = y[j][r];
+        if (r < n_rows && n[j] < a.N) as_global((float*)a.Y)[(int64_t)rm.orig(r) * a.N + n[j]] = y[j][r];
     return;
   }
-  RMSMP_PHASE(12);
+  if (a.stamps) RMSMP_PHASE(12);
+  // with a positive output scale the clamp at code 0 already does what ReLU would (a negative y
+  // rounds to a non-positive value), so the separate maximum is skipped
+  const bool relu_q = relu && !(a.out_inv_scale > 0.0f);
   uint32_t packed[NB][2];
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
-    packed[j][0] = packed[j][1] = 0u;
-#pragma unroll
-    for (int r = 0; r < 16; ++r)
-      packed[j][r >> 3] |= requant_u4(dequant(v[j][r], m[r], has_bias, bias[r], relu), a.out_inv_scale) << (4 * (r & 7));
+    if (has_bias) {
+      if (relu_q)
+        requant_block<true, true>(v[j], m, bias, a.out_inv_scale, packed[j]);
+      else
+        requant_block<true, false>(v[j], m, bias, a.out_inv_scale, packed[j]);
+    } else {
+      if (relu_q)
+        requant_block<false, true>(v[j], m, bias, a.out_inv_scale, packed[j]);
+      else
+        requant_block<false, false>(v[j], m, bias, a.out_inv_scale, packed[j]);
+    }
   }
-  RMSMP_PHASE(13);
-#ifdef RMSMP_TUNE_NO_STORE
-  if (packed[0][0] != 0x12345679u) return;
-#endif
+  if (a.stamps) RMSMP_PHASE(13);
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
     if (n[j] >= a.N) continue;
     // the first grouped position of a lane is a multiple of 16
-    uint8_t* dst = (uint8_t*)a.Y + n[j] * (a.M / 2) + (rm.m[0].w >> 1);
+    RMSMP_GLOBAL uint8_t* dst = as_global((uint8_t*)a.Y) + n[j] * (a.M / 2) + (rm.gpos0() >> 1);
     if (n_rows == 16 && (((uintptr_t)dst) & 7) == 0) {
-      *(uint2*)dst = make_uint2(packed[j][0], packed[j][1]);
+      *(RMSMP_GLOBAL v2u*)dst = (v2u){packed[j][0], packed[j][1]};
     } else {
       for (int b = 0; b < n_rows / 2; ++b) dst[b] = (uint8_t)(packed[j][b >> 2] >> (8 * (b & 3)));
     }
   }
+  if (a.stamps) RMSMP_PHASE(9);
 }
 
 __device__ __forceinline__ int lane_rows(int nvalid, int lane) {
@@ -470,8 +549,12 @@ constexpr int PT_BN = 128;
 constexpr int PT_THREADS = 256;
 constexpr int PT_PATCH_UNROLL = 6;              // 16-byte patch pieces in flight per thread
 constexpr int PT_META_BYTES = 2 * TILE_M * 16;  // row metadata of the work-group's 64 rows, kept at the start of LDS
-constexpr int PT_RING = 8;                      // K steps of packed weights in flight per wave and tile
+#ifndef RMSMP_PT_RING
+#define RMSMP_PT_RING 8
+#endif
+constexpr int PT_RING = RMSMP_PT_RING;          // K steps of packed weights in flight per wave and tile
 constexpr int PT_KSPLIT = 2;                    // waves sharing one output block
+constexpr int PT_XCH_BYTES = 4 * 2 * 16 * LANES * 4;  // partial-sum exchange buffer in LDS
 
 struct PatchGeom {
   int row_stride;     // LDS bytes per patch pixel (C + 16)
@@ -485,149 +568,122 @@ __device__ __forceinline__ int fast_div(int n, uint32_t magic) {
   return magic ? (int)__umulhi((uint32_t)n, magic) : n;
 }
 
-// KIND0 / KIND1: storage classes of the work-group's two weight tiles (template parameters so
-// that the K loop has no branches).
-template <int TAPS, int CPT, int KIND0, int KIND1>
-__device__ __forceinline__ void patch_body(const GemmArgs& a, const PatchGeom& g, uint8_t* smem_raw, int mt0, int mt1,
-                                           const TileRef& tr0, const TileRef& tr1, bool two) {
-  constexpr int C = CPT * KSTEP;
+// What the prologue leaves for the per-tile-pair part of the kernel.
+struct PatchState {
+  uint8_t* meta;   // LDS: row metadata of the current tile pair (64 rows x 16 bytes)
+  uint8_t* xch;    // LDS: partial-sum exchange buffer (4 waves x 2 blocks x 4 KiB)
+  uint8_t* patch;  // LDS: decoded input patch, then the zero-point row
+  int row_addr0, row_addr1;  // per 32-pixel block of this lane
+  uint32_t vmask0, vmask1;
+  int zaddr;
+  int n0;
+};
+
+// Everything a tile pair reads from global memory before its K loop, as raw registers: the
+// first PT_RING K steps of both weight tiles of this wave, the lookup tables of table-decoded
+// tiles and (threads 0..63) one row of metadata.  Issued as early as possible -- for the first
+// pair together with the patch, for later pairs before the previous pair's epilogue -- so that
+// the memory latency is hidden behind other work.  The tile classes are only known at run time
+// here; 4-bit fragments use the first half of a slot.
+struct PairLoads {
+  uint4 ring0[PT_RING], ring1[PT_RING];
+  uint4 T0, T1;
+  int4 meta_row;
+};
+
+template <int NSTEP>
+__device__ __forceinline__ void issue_ring(const uint8_t* wb, int kind, int lane, uint4 (&ring)[PT_RING]) {
+  if (kind == TILE_I8) {
+#pragma unroll
+    for (int u = 0; u < PT_RING; ++u)
+      if (u < NSTEP) ring[u] = *(const uint4*)(wb + (int64_t)u * PT_KSPLIT * (LANES * 16) + (uint32_t)lane * 16);
+  } else {
+#pragma unroll
+    for (int u = 0; u < PT_RING; ++u)
+      if (u < NSTEP) {
+        const uint2 w = *(const uint2*)(wb + (int64_t)u * PT_KSPLIT * (LANES * 8) + (uint32_t)lane * 8);
+        ring[u].x = w.x;
+        ring[u].y = w.y;
+      }
+  }
+}
+
+template <int NSTEP>
+__device__ __forceinline__ void issue_pair_loads(const GemmArgs& a, int mt0, int mt1, const TileRef& tr0, const TileRef& tr1,
+                                                 PairLoads& pl) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int kq = __builtin_amdgcn_readfirstlane(tid >> 6) >> 1;
+  issue_ring<NSTEP>(a.w.blob + tr0.blob_off + kq * (LANES * (tr0.kind == TILE_I8 ? 16 : 8)), tr0.kind, lane, pl.ring0);
+  issue_ring<NSTEP>(a.w.blob + tr1.blob_off + kq * (LANES * (tr1.kind == TILE_I8 ? 16 : 8)), tr1.kind, lane, pl.ring1);
+  if (tr0.kind == TILE_NIB_LUT) pl.T0 = *(const uint4*)(a.w.p_lut + ((int64_t)mt0 * TILE_M + tile_row_goff(lane & 31)) * 4);
+  if (tr1.kind == TILE_NIB_LUT) pl.T1 = *(const uint4*)(a.w.p_lut + ((int64_t)mt1 * TILE_M + tile_row_goff(lane & 31)) * 4);
+  // threads 0..31 fetch tile 0's rows, 32..63 tile 1's
+  if (tid < 2 * TILE_M)
+    pl.meta_row = ((const int4*)a.w.p_meta)[(tid < TILE_M ? mt0 : mt1) * TILE_M + (tid & (TILE_M - 1))];
+}
+
+template <int KIND>
+__device__ __forceinline__ typename RawFrag<KIND>::type raw_of(const uint4& r);
+template <>
+__device__ __forceinline__ uint2 raw_of<TILE_NIB_SHIFT>(const uint4& r) { return make_uint2(r.x, r.y); }
+template <>
+__device__ __forceinline__ uint2 raw_of<TILE_NIB_LUT>(const uint4& r) { return make_uint2(r.x, r.y); }
+template <>
+__device__ __forceinline__ uint4 raw_of<TILE_I8>(const uint4& r) { return r; }
+__device__ __forceinline__ void raw_into(uint4& r, uint2 w) { r.x = w.x; r.y = w.y; }
+__device__ __forceinline__ void raw_into(uint4& r, uint4 w) { r = w; }
+
+// Which pair comes after the current one in this work-group (valid == false: none).
+struct NextPair {
+  bool valid;
+  int mt0, mt1;
+  TileRef tr0, tr1;
+};
+
+// One tile pair: weight rings, K loop, partial-sum exchange, epilogue.  KIND0 / KIND1 are the
+// storage classes of the two weight tiles (template parameters so that the K loop has no
+// branches).
+template <int TAPS, int CPT, int KIND0, int KIND1, bool MULTI>
+__device__ __forceinline__ void patch_pair(const GemmArgs& a, const EpArgs& ea, const PatchGeom& g, const PatchState& ps,
+                                           PairLoads& pl, const TileRef& tr0, const TileRef& tr1, bool two,
+                                           const NextPair& next) {
   constexpr int KW = TAPS == 9 ? 3 : 1;
-  constexpr int KH = KW;
   constexpr int NKS = TAPS * CPT;
   constexpr int NSTEP = NKS / PT_KSPLIT;  // K steps per wave (CPT is even)
   constexpr int SPT = CPT / PT_KSPLIT;    // of which per tap
   static_assert(CPT % PT_KSPLIT == 0, "a tap must hold a whole number of K steps per wave");
-  RMSMP_PHASE(0);
-  const EpArgs ea = pin_epilogue_args(a);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wt = wave & 1;   // which 64-pixel half of the work-group's 128 pixels
   const int kq = wave >> 1;  // K steps kq, kq+2, ...
-  const int n0 = blockIdx.x * PT_BN;
-  const int H = a.d.H, W = a.d.W, pad = a.d.pad;
-  const int hw_out = a.OH * a.OW;
-  const int row_stride = g.row_stride, patch_rows = g.patch_rows;
+  const int W = a.d.W;
+  const int row_stride = g.row_stride;
+  const uint8_t* smem = ps.patch;
 
-  // flattened input index of tap (0,0) for output pixel n (may be negative / out of image)
-  auto base_index = [&](int n, int& oh, int& ow) -> int {
-    const int b = fast_div(n, g.magic_hw);
-    const int rem = n - b * hw_out;
-    oh = fast_div(rem, g.magic_ow);
-    ow = rem - oh * a.OW;
-    return (b * H + (oh - pad)) * W + (ow - pad);
-  };
-  int toh, tow;
-  int f_lo = base_index(n0, toh, tow);
-  if (f_lo < 0) f_lo = 0;
-
-  // ---- 1. the patch loads go out first: the main loop cannot start before the patch has been
-  // decoded into LDS.  Pixels f_lo .. f_lo+patch_rows-1 are one contiguous byte range of X;
-  // piece idx (32 channels, 16 bytes) sits at byte 16*idx of it and goes, decoded to int8, to LDS
-  // byte 32*idx + 16*(idx / pieces-per-pixel) (rows are padded by 16 bytes).  Reads past the end
-  // of X are clamped (those rows are never used).
-  const uint8_t* X = (const uint8_t*)a.X;
-  constexpr int PIECES = C / 32;
-  const int total = patch_rows * PIECES;
-  const int64_t x_bytes = (int64_t)a.d.B * H * W * (C / 2);
-  const int64_t src0 = (int64_t)f_lo * (C / 2);
-  uint4 pw[PT_PATCH_UNROLL];
-#pragma unroll
-  for (int u = 0; u < PT_PATCH_UNROLL; ++u) {
-    int64_t off = src0 + (int64_t)(u * PT_THREADS + tid) * 16;
-    off = off < x_bytes - 16 ? off : x_bytes - 16;
-    pw[u] = *(const uint4*)(X + off);
-  }
-
-  // ---- 2. weight rings of the two tiles, lookup tables, row metadata
+  // ---- the weight rings were filled by issue_pair_loads; this wave's K steps continue from there
   constexpr int fb0 = KIND0 == TILE_I8 ? 16 : 8, fb1 = KIND1 == TILE_I8 ? 16 : 8;
   constexpr int step0 = LANES * fb0, step1 = LANES * fb1;  // bytes per K step
   // uniform base of this wave's first K step + 32-bit lane offset; stepping through K is scalar work
   const uint8_t* const wb0 = a.w.blob + tr0.blob_off + kq * step0;
   const uint8_t* const wb1 = a.w.blob + tr1.blob_off + kq * step1;
   const uint32_t wl0 = (uint32_t)lane * fb0, wl1 = (uint32_t)lane * fb1;
-  typename RawFrag<KIND0>::type ring0[PT_RING];
-  typename RawFrag<KIND1>::type ring1[PT_RING];
-#pragma unroll
-  for (int u = 0; u < PT_RING; ++u) {
-    if (u < NSTEP) {
-      ring0[u] = load_raw<KIND0>(wb0 + (int64_t)u * PT_KSPLIT * step0, wl0);
-      ring1[u] = load_raw<KIND1>(wb1 + (int64_t)u * PT_KSPLIT * step1, wl1);
-    }
-  }
-  uint4 T0 = make_uint4(0, 0, 0, 0), T1 = T0;
-  if (KIND0 == TILE_NIB_LUT) T0 = *(const uint4*)(a.w.p_lut + ((int64_t)mt0 * TILE_M + tile_row_goff(lane & 31)) * 4);
-  if (KIND1 == TILE_NIB_LUT) T1 = *(const uint4*)(a.w.p_lut + ((int64_t)mt1 * TILE_M + tile_row_goff(lane & 31)) * 4);
-  // row metadata: threads 0..31 fetch tile 0's rows, 32..63 tile 1's; parked in LDS until the end
-  int4 meta_row = make_int4(0, 0, -1, -1);
-  if (tid < 2 * TILE_M) meta_row = ((const int4*)a.w.p_meta)[(tid < TILE_M ? mt0 : mt1) * TILE_M + (tid & (TILE_M - 1))];
-  uint8_t* const smem_meta = smem_raw;
-  uint8_t* const smem = smem_raw + PT_META_BYTES;  // the patch, later the exchange buffer
-  RMSMP_PHASE(8);
+  const uint4 T0 = pl.T0, T1 = pl.T1;
 
-  // decode the patch pieces into LDS; a patch larger than one batch takes more rounds
-  {
-    auto put_piece = [&](int idx, uint4 w) {
-      uint8_t* dst = smem + idx * 32 + (idx / PIECES) * 16;
-      *(v4i*)dst = decode_act_u4(make_uint2(w.x, w.y));
-      *(v4i*)(dst + 16) = decode_act_u4(make_uint2(w.z, w.w));
-    };
-    RMSMP_PHASE(7);
-#pragma unroll
-    for (int u = 0; u < PT_PATCH_UNROLL; ++u) {
-      const int idx = u * PT_THREADS + tid;
-      if (idx < total) put_piece(idx, pw[u]);
-    }
-#pragma unroll 1
-    for (int base = PT_THREADS * PT_PATCH_UNROLL; base < total; base += PT_THREADS) {
-      const int idx = base + tid;
-      int64_t off = src0 + (int64_t)idx * 16;
-      off = off < x_bytes - 16 ? off : x_bytes - 16;
-      const uint4 w = *(const uint4*)(X + off);
-      if (idx < total) put_piece(idx, w);
-    }
-    // a constant row behind the patch: the zero-point code, for out-of-image taps
-    const uint32_t zf = 0x01010101u * (uint32_t)(a.ep.act_zero_point & 15);
-    if (tid < C / 16) *(v4i*)(smem + patch_rows * row_stride + tid * 16) = (v4i){(int)zf, (int)zf, (int)zf, (int)zf};
-    if (tid < 2 * TILE_M) *(int4*)(smem_meta + tid * 16) = meta_row;
-  }
-  RMSMP_PHASE(11);
-
-  // ---- 3. per lane and 32-pixel block: LDS address of tap (0,0) and the taps inside the image.
-  // Validity is separable: tap (kh,kw) is inside iff kh is in [kh_lo,kh_hi] and kw in [kw_lo,kw_hi].
-  const int lane_off = 16 * (lane >> 5) + kq * KSTEP;
-  const int zaddr = patch_rows * row_stride + lane_off;
-  int row_addr[2];
-  uint32_t vmask[2];
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int n = n0 + 64 * wt + 32 * j + (lane & 31);
-    const bool n_ok = n < (int)a.N;
-    int oh = 0, ow = 0;
-    const int f0 = base_index(n_ok ? n : n0, oh, ow);
-    const int kw_lo = max(0, pad - ow), kw_hi = min(KW - 1, W - 1 + pad - ow);
-    const int kh_lo = max(0, pad - oh), kh_hi = min(KH - 1, H - 1 + pad - oh);
-    const uint32_t wbits = kw_hi >= kw_lo ? ((2u << kw_hi) - (1u << kw_lo)) : 0u;  // bits kw_lo..kw_hi
-    uint32_t m = 0;
-#pragma unroll
-    for (int kh = 0; kh < KH; ++kh) m |= (kh >= kh_lo && kh <= kh_hi) ? wbits << (KW * kh) : 0u;
-    vmask[j] = n_ok ? m : 0u;
-    row_addr[j] = (f0 - f_lo) * row_stride + lane_off;
-  }
   // LDS address of this lane's B fragment of pixel block j at tap t.  The tap of a step is known
   // at compile time (the same for both waves of a block); steps inside a tap differ by an
   // immediate offset and the per-wave part kq*KSTEP sits in the lane offsets.
   const int tap_row_bytes = W * row_stride;
   auto tap_base = [&](int t, int j) -> int {
     const int kh = t / KW, kw = t - kh * KW;
-    return ((vmask[j] >> t) & 1u) ? row_addr[j] + kh * tap_row_bytes + kw * row_stride : zaddr;
+    const uint32_t vm = j ? ps.vmask1 : ps.vmask0;
+    const int ra = j ? ps.row_addr1 : ps.row_addr0;
+    return ((vm >> t) & 1u) ? ra + kh * tap_row_bytes + kw * row_stride : ps.zaddr;
   };
 
-  RMSMP_PHASE(1);
-  __syncthreads();  // patch is in LDS
   RMSMP_PHASE(2);
-
-  // ---- 4. main loop over this wave's K steps; B fragments are fetched one step ahead
+  // ---- main loop over this wave's K steps; B fragments are fetched one step ahead
   v16i acc[2][2];  // [weight tile][pixel block]
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -644,11 +700,11 @@ __device__ __forceinline__ void patch_body(const GemmArgs& a, const PatchGeom& g
     // the matrix pipe takes one MFMA every 32 cycles, so four MFMAs in a row would block the
     // wave for 96 cycles; the scheduling groups below ask for the step's vector instructions to
     // be spread between its MFMAs instead, where they issue for free.
-    v4i av0 = decode_raw<KIND0>(ring0[0], T0);
-    v4i av1 = decode_raw<KIND1>(ring1[0], T1);
+    v4i av0 = decode_raw<KIND0>(raw_of<KIND0>(pl.ring0[0]), T0);
+    v4i av1 = decode_raw<KIND1>(raw_of<KIND1>(pl.ring1[0]), T1);
     if (PT_RING < NSTEP) {
-      ring0[0] = load_raw<KIND0>(wb0 + (int64_t)PT_RING * PT_KSPLIT * step0, wl0);
-      ring1[0] = load_raw<KIND1>(wb1 + (int64_t)PT_RING * PT_KSPLIT * step1, wl1);
+      raw_into(pl.ring0[0], load_raw<KIND0>(wb0 + (int64_t)PT_RING * PT_KSPLIT * step0, wl0));
+      raw_into(pl.ring1[0], load_raw<KIND1>(wb1 + (int64_t)PT_RING * PT_KSPLIT * step1, wl1));
     }
     constexpr int NV0 = KIND0 == TILE_NIB_SHIFT ? 6 : KIND0 == TILE_NIB_LUT ? 22 : 0;
     constexpr int NV1 = KIND1 == TILE_NIB_SHIFT ? 6 : KIND1 == TILE_NIB_LUT ? 22 : 0;
@@ -658,11 +714,11 @@ __device__ __forceinline__ void patch_body(const GemmArgs& a, const PatchGeom& g
       v4i nav0 = av0, nav1 = av1, nb0 = b0, nb1 = b1;
       if (i + 1 < NSTEP) {
         const int u = (i + 1) % PT_RING;
-        nav0 = decode_raw<KIND0>(ring0[u], T0);
-        nav1 = decode_raw<KIND1>(ring1[u], T1);
+        nav0 = decode_raw<KIND0>(raw_of<KIND0>(pl.ring0[u]), T0);
+        nav1 = decode_raw<KIND1>(raw_of<KIND1>(pl.ring1[u]), T1);
         if (i + 1 + PT_RING < NSTEP) {
-          ring0[u] = load_raw<KIND0>(wb0 + (int64_t)(i + 1 + PT_RING) * PT_KSPLIT * step0, wl0);
-          ring1[u] = load_raw<KIND1>(wb1 + (int64_t)(i + 1 + PT_RING) * PT_KSPLIT * step1, wl1);
+          raw_into(pl.ring0[u], load_raw<KIND0>(wb0 + (int64_t)(i + 1 + PT_RING) * PT_KSPLIT * step0, wl0));
+          raw_into(pl.ring1[u], load_raw<KIND1>(wb1 + (int64_t)(i + 1 + PT_RING) * PT_KSPLIT * step1, wl1));
         }
         if ((i + 1) % SPT == 0) {
           cur0 = tap_base((i + 1) / SPT, 0);
@@ -699,80 +755,276 @@ __device__ __forceinline__ void patch_body(const GemmArgs& a, const PatchGeom& g
   }
 
   RMSMP_PHASE(3);
-  // ---- 5. add the two partial sums of a block.  Wave kq finishes weight tile kq of the block
-  // (both pixel blocks) and hands the other tile's partial sums to its partner.
-  __syncthreads();  // everyone is done with the patch; LDS is reused for the exchange
-  RMSMP_PHASE(4);
-  {
-    int* dst = (int*)smem + wave * (2 * 16 * LANES);  // slot [giver wave][pixel block]
+  // ---- the rings are drained: start the next pair's reads now, behind the exchange and epilogue
+  if (MULTI && next.valid) issue_pair_loads<NSTEP>(a, next.mt0, next.mt1, next.tr0, next.tr1, pl);
+  // ---- add the two partial sums of a block.  Wave kq finishes weight tile kq of the block
+  // (both pixel blocks) and hands the other tile's partial sums to its partner.  The two roles
+  // are two copies of the code under a wave-uniform branch, so that which accumulators are
+  // given and which are kept is static (selecting them per element costs 64 instructions).
+  if (!MULTI) __syncthreads();  // the exchange buffer overlays the patch: every wave is done reading it
+  v16i mine[2];
+  auto exchange = [&](const v16i (&give)[2], const v16i (&keep)[2]) {
+    int* dst = (int*)ps.xch + wave * (2 * 16 * LANES);  // slot [giver wave][pixel block]
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        v4i give;
+        v4i gq;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) give[e] = kq ? acc[0][j][4 * q + e] : acc[1][j][4 * q + e];
-        *(v4i*)(dst + j * (16 * LANES) + q * (4 * LANES) + lane * 4) = give;
+        for (int e = 0; e < 4; ++e) gq[e] = give[j][4 * q + e];
+        *(v4i*)(dst + j * (16 * LANES) + q * (4 * LANES) + lane * 4) = gq;
       }
-  }
-  __syncthreads();
-  if (kq == 1 && !two) return;
-  v16i mine[2];
-  {
-    const int* src = (const int*)smem + (wave ^ 2) * (2 * 16 * LANES);
+    __syncthreads();
+    RMSMP_PHASE(4);
+    const int* src = (const int*)ps.xch + (wave ^ 2) * (2 * 16 * LANES);
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const v4i got = *(const v4i*)(src + j * (16 * LANES) + q * (4 * LANES) + lane * 4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) mine[j][4 * q + e] = (kq ? acc[1][j][4 * q + e] : acc[0][j][4 * q + e]) + got[e];
+        for (int e = 0; e < 4; ++e) mine[j][4 * q + e] = keep[j][4 * q + e] + got[e];
       }
+  };
+  if (kq == 0)
+    exchange(acc[1], acc[0]);
+  else
+    exchange(acc[0], acc[1]);
+  if (!(kq == 1 && !two)) {
+    RMSMP_PHASE(5);
+    RowMetaLds rm;
+    rm.base = (const int*)__builtin_assume_aligned((const int*)ps.meta + kq * TILE_M + 16 * (lane >> 5), 64);
+    rm.rows = 2 * TILE_M;
+    const int n_rows = lane_rows(kq ? tr1.nvalid : tr0.nvalid, lane);
+    const int kind = kq ? KIND1 : KIND0;
+    const int64_t ncol[2] = {(int64_t)ps.n0 + 64 * wt + (lane & 31), (int64_t)ps.n0 + 64 * wt + 32 + (lane & 31)};
+    finish_tiles<2>(ea, kind, mine, rm, n_rows, ncol);
   }
-  RMSMP_PHASE(5);
-  RowMeta rm;
-  {
-    const int4* src = (const int4*)smem_meta + kq * TILE_M + 16 * (lane >> 5);
-#pragma unroll
-    for (int r = 0; r < 16; ++r) rm.m[r] = src[r];
-  }
-  const int n_rows = lane_rows(kq ? tr1.nvalid : tr0.nvalid, lane);
-  const int kind = kq ? KIND1 : KIND0;
-  const int64_t ncol[2] = {(int64_t)n0 + 64 * wt + (lane & 31), (int64_t)n0 + 64 * wt + 32 + (lane & 31)};
-  finish_tiles<2>(ea, kind, mine, rm, n_rows, ncol);
   RMSMP_PHASE(6);
 }
 
-template <int TAPS, int CPT>
-__global__ __launch_bounds__(PT_THREADS) void conv_patch_kernel(GemmArgs a, PatchGeom g) {
+// Everything a work-group does once, whatever its tile pairs: stage the input patch in LDS,
+// work out each lane's LDS addresses, and (behind the first batch of patch reads) start the
+// reads of the first tile pair.
+template <int TAPS, int CPT, bool MULTI>
+__device__ __forceinline__ void patch_prologue(const GemmArgs& a, const PatchGeom& g, PatchState& ps, PairLoads& pl,
+                                               int first_mt0, int first_mt1, const TileRef& first_tr0,
+                                               const TileRef& first_tr1) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
-  // tiles y and n_tiles-1-y; the middle tile of an odd count stands alone (its second tile
-  // shadows it and is never stored)
-  const int mt0 = blockIdx.y;
-  const int mt1 = a.w.n_tiles - 1 - mt0;
-  const bool two = mt1 > mt0;
-  const TileRef tr0 = tile_ref(a.w, mt0);
-  const TileRef tr1 = tile_ref(a.w, mt1);
-  // tiles are sorted by class, so kind0 <= kind1
+  constexpr int C = CPT * KSTEP;
+  constexpr int KW = TAPS == 9 ? 3 : 1;
+  constexpr int KH = KW;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wt = wave & 1;
+  const int kq = wave >> 1;
+  const int H = a.d.H, W = a.d.W, pad = a.d.pad;
+  const int hw_out = a.OH * a.OW;
+  const int row_stride = g.row_stride, patch_rows = g.patch_rows;
+  ps.meta = smem_raw + PHASE_LDS_BYTES;
+  // a work-group with one tile pair is done with the patch when it exchanges partial sums, so
+  // the exchange buffer lies over it; with several pairs the patch has to survive
+  ps.xch = ps.meta + PT_META_BYTES;
+  ps.patch = MULTI ? ps.xch + PT_XCH_BYTES : ps.xch;
+  ps.n0 = blockIdx.x * PT_BN;
+  uint8_t* const smem = ps.patch;
+
+  // flattened input index of tap (0,0) for output pixel n (may be negative / out of image)
+  auto base_index = [&](int n, int& oh, int& ow) -> int {
+    const int b = fast_div(n, g.magic_hw);
+    const int rem = n - b * hw_out;
+    oh = fast_div(rem, g.magic_ow);
+    ow = rem - oh * a.OW;
+    return (b * H + (oh - pad)) * W + (ow - pad);
+  };
+  int toh, tow;
+  int f_lo = base_index(ps.n0, toh, tow);
+  if (f_lo < 0) f_lo = 0;
+
+  constexpr int NSTEP = TAPS * CPT / PT_KSPLIT;
+
+  // ---- 1. the patch.  Pixels f_lo .. f_lo+patch_rows-1 are one contiguous byte range of X;
+  // piece idx (32 channels, 16 bytes) sits at byte 16*idx of it and goes, decoded to int8, to LDS
+  // byte 32*idx + 16*(idx / pieces-per-pixel) (rows are padded by 16 bytes).  Reads past the end
+  // of X are clamped (those rows are never used).  The first batch of loads is issued before
+  // anything else in the kernel.
+  {
+    const uint8_t* X = (const uint8_t*)a.X;
+    constexpr int PIECES = C / 32;
+    const int total = patch_rows * PIECES;
+    const int64_t x_bytes = (int64_t)a.d.B * H * W * (C / 2);
+    const int64_t src0 = (int64_t)f_lo * (C / 2);
+    auto put_piece = [&](int idx, uint4 w) {
+      uint8_t* dst = smem + idx * 32 + (idx / PIECES) * 16;
+      *(v4i*)dst = decode_act_u4(make_uint2(w.x, w.y));
+      *(v4i*)(dst + 16) = decode_act_u4(make_uint2(w.z, w.w));
+    };
+#pragma unroll 1
+    for (int base = 0; base < total; base += PT_THREADS * PT_PATCH_UNROLL) {
+      uint4 pw[PT_PATCH_UNROLL];
+#pragma unroll
+      for (int u = 0; u < PT_PATCH_UNROLL; ++u) {
+        int64_t off = src0 + (int64_t)(base + u * PT_THREADS + tid) * 16;
+        off = off < x_bytes - 16 ? off : x_bytes - 16;
+        pw[u] = *(const uint4*)(X + off);
+      }
+      // behind the first batch of patch reads: everything the first tile pair needs
+      if (base == 0) issue_pair_loads<NSTEP>(a, first_mt0, first_mt1, first_tr0, first_tr1, pl);
+      RMSMP_PHASE(7);
+#pragma unroll
+      for (int u = 0; u < PT_PATCH_UNROLL; ++u) {
+        const int idx = base + u * PT_THREADS + tid;
+        if (idx < total) put_piece(idx, pw[u]);
+      }
+    }
+    // a constant row behind the patch: the zero-point code, for out-of-image taps
+    const uint32_t zf = 0x01010101u * (uint32_t)(a.ep.act_zero_point & 15);
+    if (tid < C / 16) *(v4i*)(smem + patch_rows * row_stride + tid * 16) = (v4i){(int)zf, (int)zf, (int)zf, (int)zf};
+  }
+  RMSMP_PHASE(11);
+
+  // ---- 2. per lane and 32-pixel block: LDS address of tap (0,0) and the taps inside the image.
+  // Validity is separable: tap (kh,kw) is inside iff kh is in [kh_lo,kh_hi] and kw in [kw_lo,kw_hi].
+  const int lane_off = 16 * (lane >> 5) + kq * KSTEP;
+  ps.zaddr = patch_rows * row_stride + lane_off;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int n = ps.n0 + 64 * wt + 32 * j + (lane & 31);
+    const bool n_ok = n < (int)a.N;
+    int oh = 0, ow = 0;
+    const int f0 = base_index(n_ok ? n : ps.n0, oh, ow);
+    const int kw_lo = max(0, pad - ow), kw_hi = min(KW - 1, W - 1 + pad - ow);
+    const int kh_lo = max(0, pad - oh), kh_hi = min(KH - 1, H - 1 + pad - oh);
+    const uint32_t wbits = kw_hi >= kw_lo ? ((2u << kw_hi) - (1u << kw_lo)) : 0u;  // bits kw_lo..kw_hi
+    uint32_t m = 0;
+#pragma unroll
+    for (int kh = 0; kh < KH; ++kh) m |= (kh >= kh_lo && kh <= kh_hi) ? wbits << (KW * kh) : 0u;
+    (j ? ps.vmask1 : ps.vmask0) = n_ok ? m : 0u;
+    (j ? ps.row_addr1 : ps.row_addr0) = (f0 - f_lo) * row_stride + lane_off;
+  }
+  RMSMP_PHASE(1);
+
+}
+
+// The part of a work-group's life spent on tile pairs of one class combination: the prologue if
+// this is where the work-group starts, then pair after pair while the classes stay the same.
+// Returns the first pair not done.  A work-group normally stays inside one instance of this
+// function from start to end, so that its instruction stream is one contiguous run of code: a
+// kernel starts with cold instruction caches too, and every jump to code not yet fetched costs
+// a memory round trip.
+template <int TAPS, int CPT, int KIND0, int KIND1, bool MULTI>
+__device__ __forceinline__ int patch_body(const GemmArgs& a, const EpArgs& ea, const PatchGeom& g, PatchState& ps,
+                                          PairLoads& pl, bool first, int pi, int pair_hi) {
+  const int tid = threadIdx.x;
+  int mt0 = pi, mt1 = a.w.n_tiles - 1 - pi;
+  TileRef tr0 = tile_ref(a.w, mt0), tr1 = tile_ref(a.w, mt1);
+  if (first) patch_prologue<TAPS, CPT, MULTI>(a, g, ps, pl, mt0, mt1, tr0, tr1);
+#pragma unroll 1
+  for (;;) {
+    NextPair next;
+    next.valid = MULTI && pi + 1 < pair_hi;
+    next.mt0 = next.valid ? pi + 1 : mt0;
+    next.mt1 = a.w.n_tiles - 1 - next.mt0;
+    next.tr0 = tile_ref(a.w, next.mt0);
+    next.tr1 = tile_ref(a.w, next.mt1);
+    const bool two = mt1 > mt0;
+    // everyone is done with the previous pair's metadata and exchange buffer, and (first pair)
+    // the patch is complete
+    __syncthreads();
+    // row metadata parked in LDS until the epilogue (read after the exchange barrier)
+    if (tid < 2 * TILE_M) {
+      int* mf = (int*)ps.meta + tid;  // field by field: [field][64 rows]
+      mf[0] = pl.meta_row.x;
+      mf[2 * TILE_M] = pl.meta_row.y;
+      mf[4 * TILE_M] = pl.meta_row.z;
+      mf[6 * TILE_M] = pl.meta_row.w;
+    }
+    patch_pair<TAPS, CPT, KIND0, KIND1, MULTI>(a, ea, g, ps, pl, tr0, tr1, two, next);
+    ++pi;
+    if (!next.valid) break;
+    mt0 = next.mt0;
+    mt1 = next.mt1;
+    tr0 = next.tr0;
+    tr1 = next.tr1;
+    if (tr0.kind != KIND0 || tr1.kind != KIND1) break;
+  }
+  return pi;
+}
+
+// pairs_per_wg: how many tile pairs a work-group runs through against the same patch (large M).
+// Pair y is tile y and tile n_tiles-1-y; the middle tile of an odd count stands alone (its second
+// tile shadows it and is never stored).  Tiles are sorted by class, so kind0 <= kind1.
+// MULTI = false is the one-pair-per-work-group build: no pair loop and no prefetch of a next
+// pair, which keeps it within the register budget of two work-groups per compute unit.
+template <int TAPS, int CPT, bool MULTI>
+__device__ __forceinline__ void patch_kernel_impl(const GemmArgs& a, const PatchGeom& g, int pairs_per_wg) {
+  RMSMP_PHASE(0);
+  EpArgs ea = pin_epilogue_args(a);
+  ea.stamps = PHASE_LDS_BYTES != 0;
+  const int n_pairs = (a.w.n_tiles + 1) / 2;
+  const int pair_lo = MULTI ? blockIdx.y * pairs_per_wg : blockIdx.y;
+  const int pair_hi = MULTI ? min(pair_lo + pairs_per_wg, n_pairs) : pair_lo + 1;
+  PatchState ps;
+  PairLoads pl;
+  pl.T0 = pl.T1 = make_uint4(0, 0, 0, 0);
+  int pi = pair_lo;
+  bool first = true;
+#pragma unroll 1
+  while (pi < pair_hi) {
+    const int k0 = tile_ref(a.w, pi).kind, k1 = tile_ref(a.w, a.w.n_tiles - 1 - pi).kind;
 #define RMSMP_BODY(K0, K1) \
-  if (tr0.kind == K0 && tr1.kind == K1) return patch_body<TAPS, CPT, K0, K1>(a, g, smem_raw, mt0, mt1, tr0, tr1, two);
-  RMSMP_BODY(TILE_NIB_SHIFT, TILE_NIB_SHIFT)
-  RMSMP_BODY(TILE_NIB_SHIFT, TILE_NIB_LUT)
-  RMSMP_BODY(TILE_NIB_SHIFT, TILE_I8)
-  RMSMP_BODY(TILE_NIB_LUT, TILE_NIB_LUT)
-  RMSMP_BODY(TILE_NIB_LUT, TILE_I8)
-  RMSMP_BODY(TILE_I8, TILE_I8)
+  if (k0 == K0 && k1 == K1) pi = patch_body<TAPS, CPT, K0, K1, MULTI>(a, ea, g, ps, pl, first, pi, pair_hi);
+    RMSMP_BODY(TILE_NIB_SHIFT, TILE_NIB_SHIFT)
+    else RMSMP_BODY(TILE_NIB_SHIFT, TILE_NIB_LUT)
+    else RMSMP_BODY(TILE_NIB_SHIFT, TILE_I8)
+    else RMSMP_BODY(TILE_NIB_LUT, TILE_NIB_LUT)
+    else RMSMP_BODY(TILE_NIB_LUT, TILE_I8)
+    else RMSMP_BODY(TILE_I8, TILE_I8)
+    else break;  // classes are sorted, so no other combination exists
 #undef RMSMP_BODY
+    first = false;
+    if (!MULTI) break;
+  }
+  RMSMP_PHASE_FLUSH();
+}
+
+template <int TAPS, int CPT>
+__global__ __launch_bounds__(PT_THREADS, 2) void conv_patch_kernel(GemmArgs a, PatchGeom g) {
+  patch_kernel_impl<TAPS, CPT, false>(a, g, 1);
+}
+
+template <int TAPS, int CPT>
+__global__ __launch_bounds__(PT_THREADS) void conv_patch_multi_kernel(GemmArgs a, PatchGeom g, int pairs_per_wg) {
+  patch_kernel_impl<TAPS, CPT, true>(a, g, pairs_per_wg);
 }
 
 static uint32_t div_magic(int64_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + (uint64_t)d - 1) / (uint64_t)d); }
 
-// Geometry checks for the LDS-resident kernel; fills the LDS layout when it applies.
-static bool patch_kernel_applies(const GemmArgs& a, PatchGeom* g, size_t* lds_bytes) {
-  if (!a.conv || a.ep.act_bits != 4 || a.d.stride != 1) return false;
+// Channel counts (in K steps of 32) the LDS-resident kernel is instantiated for.
+static bool patch_cpt_supported(int taps, int cpt) {
+  if (taps == 9) return cpt == 2 || cpt == 4 || cpt == 8 || cpt == 16;
+  return cpt == 2 || cpt == 4 || cpt == 8 || cpt == 16 || cpt == 24;
+}
+
+// Geometry checks for the LDS-resident kernel.  When it applies, *pa is the argument block to
+// launch it with (a plain GEMM becomes a 1x1 convolution over N single-pixel images) and the
+// LDS layout and grid are filled in.
+static bool patch_kernel_applies(const GemmArgs& a0, GemmArgs* pa, PatchGeom* g, size_t* lds_bytes, dim3* grid,
+                                 int* pairs_per_wg) {
+  if (a0.ep.act_bits != 4) return false;
+  GemmArgs a = a0;
+  if (!a.conv) {
+    if (a.K % (2 * KSTEP) != 0 || a.K > 1024 || a.N >= ((int64_t)1 << 30)) return false;
+    a.conv = 1;
+    a.d = rmsmp_conv_desc{(int32_t)a.N, (int32_t)a.K, 1, 1, 1, 1, 1, 0};
+    a.OH = a.OW = 1;
+  }
+  if (a.d.stride != 1) return false;
   const int taps = a.d.KH * a.d.KW;
   if (!(taps == 1 || (a.d.KH == 3 && a.d.KW == 3))) return false;
-  if (a.d.C != 64 && a.d.C != 128 && a.d.C != 256 && a.d.C != 512) return false;
+  if (a.d.C % KSTEP != 0 || !patch_cpt_supported(taps, a.d.C / KSTEP)) return false;
+  if (a.w.nks != taps * (a.d.C / KSTEP)) return false;
   // the flattened input index of a tile's pixels must grow with the pixel number
   if (a.OH > a.d.H || a.OW > a.d.W) return false;
   // widest run of flattened input pixels any 128-pixel tile touches
@@ -785,19 +1037,35 @@ static bool patch_kernel_applies(const GemmArgs& a, PatchGeom* g, size_t* lds_by
   if (in_px + span >= ((int64_t)1 << 31) / (a.d.C + 16)) return false;
   const int rs = a.d.C + 16;
   const size_t need = (size_t)(span + 1) * rs;  // patch + zero-point row
-  const size_t xch = (size_t)4 * 2 * 16 * LANES * 4;
-  if (need > 150 * 1024) return false;
+  // One tile pair per work-group (the exchange buffer overlays the patch) unless the patch is so
+  // large that only one work-group fits a compute unit anyway: then a work-group keeps its patch
+  // and runs through several pairs, as long as the grid still fills the chip.
+  const size_t lds_single = PHASE_LDS_BYTES + PT_META_BYTES + (need > PT_XCH_BYTES ? need : (size_t)PT_XCH_BYTES);
+  const size_t lds_multi = PHASE_LDS_BYTES + PT_META_BYTES + PT_XCH_BYTES + need;
+  if (lds_single > 160 * 1024) return false;
+  const int64_t gx = (a.N + PT_BN - 1) / PT_BN;
+  const int n_pairs = (a.w.n_tiles + 1) / 2;
+  int64_t ppw = 1;
+  if (lds_single > 80 * 1024 && lds_multi <= 160 * 1024) {
+    ppw = gx * n_pairs / 256;
+    ppw = ppw < 1 ? 1 : ppw > n_pairs ? n_pairs : ppw;
+  }
+  const int gy = (int)((n_pairs + ppw - 1) / ppw);
+  ppw = (n_pairs + gy - 1) / gy;
   g->row_stride = rs;
   g->patch_rows = (int)span;
   g->magic_hw = div_magic(hw);
   g->magic_ow = div_magic(a.OW);
-  *lds_bytes = PT_META_BYTES + (need > xch ? need : xch);
+  *lds_bytes = ppw == 1 ? lds_single : lds_multi;
+  *pairs_per_wg = (int)ppw;
+  *grid = dim3((unsigned)gx, (unsigned)gy, 1);
+  *pa = a;
   return true;
 }
 
 // Dynamic LDS above 64 KiB must be allowed per kernel once (per device); remember what was set.
 template <int TAPS, int CPT>
-static int launch_patch_t(const GemmArgs& a, PatchGeom g, size_t lds, dim3 grid, hipStream_t s) {
+static int launch_patch_t(const GemmArgs& a, PatchGeom g, size_t lds, dim3 grid, int pairs_per_wg, hipStream_t s) {
   static bool allowed[64] = {false};
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
@@ -807,18 +1075,23 @@ static int launch_patch_t(const GemmArgs& a, PatchGeom g, size_t lds, dim3 grid,
     e = hipFuncSetAttribute((const void*)conv_patch_kernel<TAPS, CPT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             160 * 1024);
     if (e != hipSuccess) return (int)e;
+    e = hipFuncSetAttribute((const void*)conv_patch_multi_kernel<TAPS, CPT>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return (int)e;
     allowed[dev] = true;
   }
-  hipLaunchKernelGGL((conv_patch_kernel<TAPS, CPT>), grid, dim3(PT_THREADS), lds, s, a, g);
+  if (pairs_per_wg == 1)
+    hipLaunchKernelGGL((conv_patch_kernel<TAPS, CPT>), grid, dim3(PT_THREADS), lds, s, a, g);
+  else
+    hipLaunchKernelGGL((conv_patch_multi_kernel<TAPS, CPT>), grid, dim3(PT_THREADS), lds, s, a, g, pairs_per_wg);
   return (int)hipGetLastError();
 }
 
-static int launch_patch(const GemmArgs& a, PatchGeom g, size_t lds, hipStream_t s) {
-  dim3 grid((unsigned)((a.N + PT_BN - 1) / PT_BN), (unsigned)((a.w.n_tiles + 1) / 2), 1);
+static int launch_patch(const GemmArgs& a, PatchGeom g, size_t lds, dim3 grid, int pairs_per_wg, hipStream_t s) {
   const int taps = a.d.KH * a.d.KW;
   const int cpt = a.d.C / KSTEP;
 #define RMSMP_PATCH_CASE(TP, CP) \
-  if (taps == TP && cpt == CP) return launch_patch_t<TP, CP>(a, g, lds, grid, s);
+  if (taps == TP && cpt == CP) return launch_patch_t<TP, CP>(a, g, lds, grid, pairs_per_wg, s);
   RMSMP_PATCH_CASE(9, 2)
   RMSMP_PATCH_CASE(9, 4)
   RMSMP_PATCH_CASE(9, 8)
@@ -827,6 +1100,7 @@ static int launch_patch(const GemmArgs& a, PatchGeom g, size_t lds, hipStream_t 
   RMSMP_PATCH_CASE(1, 4)
   RMSMP_PATCH_CASE(1, 8)
   RMSMP_PATCH_CASE(1, 16)
+  RMSMP_PATCH_CASE(1, 24)
 #undef RMSMP_PATCH_CASE
   return (int)hipErrorInvalidValue;
 }
@@ -983,13 +1257,16 @@ static int launch_skinny_t(const GemmArgs& a, hipStream_t s) {
 int launch_gemm(const GemmArgs& a, void* stream) {
   hipStream_t s = (hipStream_t)stream;
   if (a.N <= 0) return 0;
-  if (a.conv) {
+  if (!a.conv && skinny_applies(a)) return a.N <= 32 ? launch_skinny_t<1>(a, s) : launch_skinny_t<2>(a, s);
+  {
+    GemmArgs pa;
     PatchGeom g;
     size_t lds;
-    if (patch_kernel_applies(a, &g, &lds)) return launch_patch(a, g, lds, s);
-    return a.ep.act_bits == 4 ? launch_general<4, true, true>(a, s) : launch_general<8, true, true>(a, s);
+    dim3 grid;
+    int ppw;
+    if (patch_kernel_applies(a, &pa, &g, &lds, &grid, &ppw)) return launch_patch(pa, g, lds, grid, ppw, s);
   }
-  if (skinny_applies(a)) return a.N <= 32 ? launch_skinny_t<1>(a, s) : launch_skinny_t<2>(a, s);
+  if (a.conv) return a.ep.act_bits == 4 ? launch_general<4, true, true>(a, s) : launch_general<8, true, true>(a, s);
   const bool vec = (a.K % 16) == 0;
   if (a.ep.act_bits == 4) return vec ? launch_general<4, false, true>(a, s) : launch_general<4, false, false>(a, s);
   return vec ? launch_general<8, false, true>(a, s) : launch_general<8, false, false>(a, s);

@@ -136,6 +136,31 @@ def test_gemm_bias_relu_requant_grouped_output(rm, oracle, M, K, N):
     p.free()
 
 
+@pytest.mark.parametrize("M,K,N", [(70, 64, 129), (130, 128, 300), (2000, 256, 5000), (96, 512, 1000), (333, 768, 257), (1030, 768, 4100),
+                                   (33, 768, 128)])
+def test_gemm_lds_resident_activation_kernel(rm, oracle, M, K, N):
+    """Shapes whose K is one of the widths the LDS-resident kernel is built for (including a weight
+    matrix tall enough that one work-group runs through several tile pairs, an odd tile count and
+    ragged M and N), with a zero point; all three output kinds."""
+    rng = np.random.default_rng(M * 11 + K * 5 + N)
+    W = si.weights_rowscaled(rng, M, K)
+    scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, 35, 60, 5))
+    xq = si.act_codes_u4(rng, (N, K))
+    z = int(rng.integers(1, 15))
+    bias = (rng.standard_normal(M) * 0.5).astype(np.float32)
+    p = rm.rmsmp_pack_weights(W, scheme)
+    ref, (acc, y, _) = oracle_outputs(oracle, W, scheme, xq, z=z, s_x=0.03, bias=bias, relu=True)
+    inv = np.float32(15.0 / float(np.percentile(y, 99.9)))
+    _, (_, _, q) = oracle_outputs(oracle, W, scheme, xq, z=z, s_x=0.03, bias=bias, relu=True, inv_s_out=inv)
+    kw = dict(act_scale=0.03, act_zero_point=z, bias=bias, relu=True)
+    assert np.array_equal(run_gemm(rm, p, xq, act_scale=0.03, act_zero_point=z, out_kind=rm.OUT_INT32), acc)
+    assert_fp32_close(run_gemm(rm, p, xq, out_kind=rm.OUT_FP32, **kw), y)
+    if M % 2 == 0:
+        Yb = run_gemm(rm, p, xq, out_kind=rm.OUT_U4, out_inv_scale=inv, **kw)
+        assert np.array_equal(grouped_codes(rm, Yb, p.perm), q)
+    p.free()
+
+
 def test_gemm_int8_activations(rm, oracle):
     rng = np.random.default_rng(31)
     for M, K, N in [(64, 147, 300), (32, 256, 64)]:
