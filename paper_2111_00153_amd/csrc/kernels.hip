@@ -550,7 +550,7 @@ constexpr int PT_THREADS = 256;
 constexpr int PT_PATCH_UNROLL = 6;              // 16-byte patch pieces in flight per thread
 constexpr int PT_META_BYTES = 2 * TILE_M * 16;  // row metadata of the work-group's 64 rows, kept at the start of LDS
 #ifndef RMSMP_PT_RING
-#define RMSMP_PT_RING 8
+#define RMSMP_PT_RING 4
 #endif
 constexpr int PT_RING = RMSMP_PT_RING;          // K steps of packed weights in flight per wave and tile
 constexpr int PT_KSPLIT = 2;                    // waves sharing one output block
@@ -860,6 +860,7 @@ __device__ __forceinline__ void patch_prologue(const GemmArgs& a, const PatchGeo
       *(v4i*)dst = decode_act_u4(make_uint2(w.x, w.y));
       *(v4i*)(dst + 16) = decode_act_u4(make_uint2(w.z, w.w));
     };
+    RMSMP_PHASE(15);
 #pragma unroll 1
     for (int base = 0; base < total; base += PT_THREADS * PT_PATCH_UNROLL) {
       uint4 pw[PT_PATCH_UNROLL];
@@ -962,6 +963,7 @@ __device__ __forceinline__ void patch_kernel_impl(const GemmArgs& a, const Patch
   RMSMP_PHASE(0);
   EpArgs ea = pin_epilogue_args(a);
   ea.stamps = PHASE_LDS_BYTES != 0;
+  RMSMP_PHASE(14);
   const int n_pairs = (a.w.n_tiles + 1) / 2;
   const int pair_lo = MULTI ? blockIdx.y * pairs_per_wg : blockIdx.y;
   const int pair_hi = MULTI ? min(pair_lo + pairs_per_wg, n_pairs) : pair_lo + 1;
