@@ -69,6 +69,9 @@ rmsmp_status rmsmp_assign_by_variance(const float* W, int64_t M, int64_t K, int6
  *   alpha   HOST fp32 [M] or NULL.  NULL: alpha_r = max_k |W[r][k]| (an all-zero row
  *           uses 1).  Weights outside [-alpha, alpha] are clipped (Section 3.1.1).
  *   taps    KH*KW for a convolution layer, 1 for a plain GEMM layer.  K % taps == 0.
+ *           A convolution layer with at most 4 input channels (K/taps <= 4) and taps a
+ *           square number up to 64 is stored for a square KW x KW filter: it can only be
+ *           used with rmsmp_conv2d and KH == KW (EUNSUPPORTED otherwise).
  *   in_perm HOST int32 [K/taps] or NULL: the order in which the input channels arrive.
  *           Channel position j of the activation tensor holds original channel in_perm[j]
  *           (use the row permutation of the layer that produced the activations when that
@@ -167,9 +170,10 @@ typedef struct {
  *       Pixels outside the image count as real value 0, i.e. code act_zero_point.
  *   Y   out_kind 0/1: [M][B*OH*OW];  out_kind 2: [B][OH][OW][M/2] bytes (NHWC, grouped rows).
  *   workspace  DEVICE scratch of at least rmsmp_conv2d_workspace_size() bytes, or NULL when
- *       that size is 0.  Layers whose C is a multiple of 16 run without workspace:
- *       the im2col matrix is never materialised.  Other layers materialise it there.
- * Errors: EINVAL, ESHAPE (K mismatch, empty output), EWORKSPACE, EHIP.
+ *       that size is 0.  Layers whose C is a multiple of 16, and 8-bit layers with at
+ *       most 4 input channels (a network's first layer), run without workspace: the
+ *       im2col matrix is never materialised.  Other layers materialise it there.
+ * Errors: EINVAL, ESHAPE (K mismatch, empty output), EWORKSPACE, EUNSUPPORTED, EHIP.
  */
 rmsmp_status rmsmp_conv2d(const rmsmp_packed* Wp, const void* X, const rmsmp_conv_desc* d,
                           const rmsmp_epilogue* ep, void* Y, void* workspace, size_t workspace_bytes,

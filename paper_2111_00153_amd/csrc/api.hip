@@ -108,6 +108,7 @@ rmsmp_status rmsmp_pack_weights(const float* W, int64_t M, int64_t K, const uint
   p->dev.p_lut = (const uint32_t*)put(h.p_lut.data(), h.p_lut.size() * 4, n_lut);
   p->dev.n_tiles = (int32_t)h.tiles.size();
   p->dev.nks = (int32_t)h.nks;
+  p->dev.k_layout = h.k_layout;
   for (const auto& t : h.tiles) {
     p->dev.class_tiles[t.kind] += 1;
     p->dev.class_rows[t.kind] += t.nvalid;
@@ -191,6 +192,8 @@ rmsmp_status rmsmp_gemm(const rmsmp_packed* Wp, const void* X, int64_t N, const 
   if (N < 0) return fail(RMSMP_ESHAPE, "gemm: N < 0");
   if (N == 0) return RMSMP_OK;
   if (!X || !Y) return fail(RMSMP_EINVAL, "gemm: NULL X or Y");
+  if (Wp->host.k_layout != rmsmp::K_TAP_CHANNEL)
+    return fail(RMSMP_EUNSUPPORTED, "gemm: these weights are stored for a small-channel convolution; use rmsmp_conv2d");
   if (ep->act_bits == 4 && (Wp->host.K & 1)) return fail(RMSMP_ESHAPE, "gemm: 4-bit activations need an even K");
   if (((uintptr_t)X & 15) != 0) return fail(RMSMP_EINVAL, "gemm: X must be 16-byte aligned");
   if (N > (int64_t)0x7fffffff * 64) return fail(RMSMP_ESHAPE, "gemm: N too large");
@@ -216,6 +219,8 @@ static rmsmp_status conv_geometry(const rmsmp_packed* Wp, const rmsmp_conv_desc*
   if ((int64_t)d->C * d->KH * d->KW != Wp->host.K || d->KH * d->KW != Wp->host.taps)
     return fail(RMSMP_ESHAPE, "conv2d: C*KH*KW and KH*KW must match the packed layer's K and taps");
   if (act_bits == 4 && (d->C & 1)) return fail(RMSMP_ESHAPE, "conv2d: 4-bit activations need an even C");
+  if (Wp->host.k_layout == rmsmp::K_FILTER_ROWS && d->KH != d->KW)
+    return fail(RMSMP_EUNSUPPORTED, "conv2d: layers with at most 4 input channels are stored for square filters");
   const int oh = (d->H + 2 * d->pad - d->KH) / d->stride + 1;
   const int ow = (d->W + 2 * d->pad - d->KW) / d->stride + 1;
   if (d->H + 2 * d->pad < d->KH || d->W + 2 * d->pad < d->KW || oh < 1 || ow < 1)
@@ -226,7 +231,13 @@ static rmsmp_status conv_geometry(const rmsmp_packed* Wp, const rmsmp_conv_desc*
 }
 
 // im2col is done on the fly whenever a 16-channel chunk is one aligned load
-static bool conv_is_implicit(const rmsmp_conv_desc* d) { return d->C % 16 == 0; }
+// Which path a convolution takes.  Implicit: the kernels address the NHWC input themselves (any
+// layer whose channel count is a multiple of 16, and 8-bit small-channel layers stored with one
+// K step per filter row).  Otherwise the lowered matrix is written to the caller's workspace.
+static bool conv_is_implicit(const rmsmp_packed* Wp, const rmsmp_conv_desc* d, int32_t act_bits) {
+  if (Wp->host.k_layout == rmsmp::K_FILTER_ROWS) return act_bits == 8 && d->stride <= 8;
+  return d->C % 16 == 0;
+}
 
 rmsmp_status rmsmp_conv2d_workspace_size(const rmsmp_packed* Wp, const rmsmp_conv_desc* d, int32_t act_bits,
                                          size_t* bytes) {
@@ -235,7 +246,7 @@ rmsmp_status rmsmp_conv2d_workspace_size(const rmsmp_packed* Wp, const rmsmp_con
   int OH, OW;
   rmsmp_status st = conv_geometry(Wp, d, act_bits, &OH, &OW);
   if (st != RMSMP_OK) return st;
-  if (conv_is_implicit(d)) {
+  if (conv_is_implicit(Wp, d, act_bits)) {
     *bytes = 0;
     return RMSMP_OK;
   }
@@ -266,7 +277,7 @@ rmsmp_status rmsmp_conv2d(const rmsmp_packed* Wp, const void* X, const rmsmp_con
   a.d = *d;
   a.OH = OH;
   a.OW = OW;
-  if (conv_is_implicit(d)) {
+  if (conv_is_implicit(Wp, d, ep->act_bits)) {
     a.K = Wp->host.K;
     a.X = X;
     a.conv = 1;
@@ -288,6 +299,7 @@ rmsmp_status rmsmp_conv2d(const rmsmp_packed* Wp, const void* X, const rmsmp_con
     ia.Kpad = Wp->host.Kpad;
     ia.act_bits = ep->act_bits;
     ia.zero_point = ep->act_zero_point;
+    ia.k_layout = Wp->host.k_layout;
     hipError_t e = (hipError_t)rmsmp::launch_im2col(ia, stream);
     if (e != hipSuccess) return hip_fail(e, "conv2d: im2col launch");
     a.K = Wp->host.Kpad;

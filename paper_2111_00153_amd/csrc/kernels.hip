@@ -1256,9 +1256,148 @@ static int launch_skinny_t(const GemmArgs& a, hipStream_t s) {
   return (int)hipGetLastError();
 }
 
+// ---------------------------------------------------------------- small-channel convolution
+//
+// A network's first layer: 8-bit activations, at most four input channels, a square filter of up
+// to 8x8, any stride.  Its lowered matrix would be by far the largest tensor of the layer (K =
+// 147 bytes per output pixel against 3 bytes per input pixel), so nothing is lowered: a
+// work-group stages the input pixels of an 8 x 16 tile of output pixels in LDS, each pixel padded
+// to four bytes, and reads B fragments straight from there.  The weights are stored with one K
+// step per filter row (KLayout K_FILTER_ROWS), so the 16 bytes a lane needs for K step kh are
+// four consecutive staged pixels of input row oh*stride - pad + kh.
+//
+// Four waves; wave w owns output rows 2w, 2w+1 of the tile (32 pixels) and goes through the
+// layer's weight tiles one at a time.  A lane's B fragments (one per filter row) are read from
+// LDS once and kept; per weight tile it then loads KH weight fragments, issues KH MFMAs and runs
+// the epilogue, with the row metadata of all tiles staged in LDS at the start.  Few registers,
+// so several work-groups share a compute unit and hide each other's memory latency.
+constexpr int CR_TH = 8, CR_TW = 16;
+constexpr int CR_MAX_TILES = 64;  // row metadata of all tiles sits in LDS (512 bytes per tile)
+
+// KHW: filter height = width as a compile-time constant (3, 5, 7), or 0 for any size up to 8.
+template <int KHW_T>
+__global__ __launch_bounds__(256, 3) void conv_rows_kernel(GemmArgs a, int tiles_w, int tiles_h) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+  const EpArgs ea = pin_epilogue_args(a);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  constexpr int KMAX = KHW_T ? KHW_T : 8;
+  const int KHW = KHW_T ? KHW_T : a.d.KH;
+  const int S = a.d.stride, C = a.d.C, H = a.d.H, W = a.d.W;
+  int blk = blockIdx.x;
+  const int tw = blk % tiles_w;
+  blk /= tiles_w;
+  const int th = blk % tiles_h;
+  const int b = blk / tiles_h;
+  const int oh0 = th * CR_TH, ow0 = tw * CR_TW;
+  const int PH = S * (CR_TH - 1) + KHW;  // staged rows
+  const int PW = S * (CR_TW - 1) + 8;    // staged pixels per row (a fragment reads 8 pixels from its first)
+  const int ih0 = oh0 * S - a.d.pad, iw0 = ow0 * S - a.d.pad;
+  int* const meta = (int*)(smem_raw + (size_t)PH * PW * 4);  // [tile][field][32 rows]
+
+  // ---- stage the input pixels, four bytes each (missing channels 0, out-of-image = zero point)
+  {
+    const uint8_t* X = (const uint8_t*)a.X;
+    const uint32_t z = (uint32_t)a.ep.act_zero_point & 255u;
+    uint32_t zfill = 0u;
+    for (int c = 0; c < C; ++c) zfill |= z << (8 * c);
+    for (int idx = tid; idx < PH * PW; idx += 256) {
+      const int py = idx / PW, px = idx - py * PW;
+      const int ih = ih0 + py, iw = iw0 + px;
+      uint32_t v = zfill;
+      if (ih >= 0 && ih < H && iw >= 0 && iw < W) {
+        const uint8_t* src = X + (((int64_t)b * H + ih) * W + iw) * C;
+        v = 0u;
+        for (int c = 0; c < C; ++c) v |= (uint32_t)src[c] << (8 * c);
+      }
+      ((uint32_t*)smem_raw)[idx] = v;
+    }
+    for (int idx = tid; idx < a.w.n_tiles * TILE_M; idx += 256) {
+      const int4 m = ((const int4*)a.w.p_meta)[idx];
+      int* dst = meta + (idx / TILE_M) * (4 * TILE_M) + (idx % TILE_M);
+      dst[0] = m.x;
+      dst[TILE_M] = m.y;
+      dst[2 * TILE_M] = m.z;
+      dst[3 * TILE_M] = m.w;
+    }
+  }
+  __syncthreads();
+
+  // this lane's output pixel and its B fragments: four consecutive staged pixels per filter row
+  const int pr = 2 * wave + ((lane & 31) >> 4), pc = lane & 15;
+  const int oh = oh0 + pr, ow = ow0 + pc;
+  const bool px_ok = oh < a.OH && ow < a.OW;
+  const int64_t n = px_ok ? ((int64_t)b * a.OH + oh) * a.OW + ow : a.N;  // a.N = no store
+  const uint32_t* sp = (const uint32_t*)smem_raw + (pr * S) * PW + pc * S + 4 * (lane >> 5);
+  v4i bf[KMAX];
+#pragma unroll
+  for (int kh = 0; kh < KMAX; ++kh) {
+    const uint32_t* q = sp + (kh < KHW ? kh : 0) * PW;
+    bf[kh] = reorder_act_i8(make_uint4(q[0], q[1], q[2], q[3]));
+  }
+
+#pragma unroll 1
+  for (int mt = 0; mt < a.w.n_tiles; ++mt) {
+    const TileRef tr = tile_ref(a.w, mt);
+    const uint8_t* wp = a.w.blob + tr.blob_off;
+    v4i af[KMAX];
+    // filter rows beyond KHW (generic build only) repeat row 0 and are not multiplied
+    if (tr.kind == TILE_I8) {
+#pragma unroll
+      for (int kh = 0; kh < KMAX; ++kh)
+        af[kh] = decode_raw<TILE_I8>(load_raw<TILE_I8>(wp, (uint32_t)((kh < KHW ? kh : 0) * LANES + lane) * 16),
+                                     make_uint4(0, 0, 0, 0));
+    } else if (tr.kind == TILE_NIB_SHIFT) {
+#pragma unroll
+      for (int kh = 0; kh < KMAX; ++kh)
+        af[kh] = decode_raw<TILE_NIB_SHIFT>(
+            load_raw<TILE_NIB_SHIFT>(wp, (uint32_t)((kh < KHW ? kh : 0) * LANES + lane) * 8), make_uint4(0, 0, 0, 0));
+    } else {
+      const uint4 T = *(const uint4*)(a.w.p_lut + ((int64_t)mt * TILE_M + tile_row_goff(lane & 31)) * 4);
+#pragma unroll
+      for (int kh = 0; kh < KMAX; ++kh)
+        af[kh] = decode_raw<TILE_NIB_LUT>(load_raw<TILE_NIB_LUT>(wp, (uint32_t)((kh < KHW ? kh : 0) * LANES + lane) * 8), T);
+    }
+    v16i acc[1];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[0][r] = 0;
+#pragma unroll
+    for (int kh = 0; kh < KMAX; ++kh)
+      if (kh < KHW) acc[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[kh], bf[kh], acc[0], 0, 0, 0);
+    RowMetaLds rm;
+    rm.base = (const int*)__builtin_assume_aligned(meta + mt * (4 * TILE_M) + 16 * (lane >> 5), 64);
+    rm.rows = TILE_M;
+    const int64_t ncol[1] = {n};
+    finish_tiles<1>(ea, tr.kind, acc, rm, lane_rows(tr.nvalid, lane), ncol);
+  }
+}
+
+static bool conv_rows_applies(const GemmArgs& a) {
+  return a.conv && a.w.k_layout == K_FILTER_ROWS && a.ep.act_bits == 8 && a.d.KH == a.d.KW && a.d.KW <= 8 && a.d.C <= 4 &&
+         a.w.nks >= a.d.KH && a.d.stride <= 8 && a.w.n_tiles <= CR_MAX_TILES;
+}
+
+static int launch_conv_rows(const GemmArgs& a, hipStream_t s) {
+  const int tiles_w = (a.OW + CR_TW - 1) / CR_TW, tiles_h = (a.OH + CR_TH - 1) / CR_TH;
+  const int64_t blocks = (int64_t)a.d.B * tiles_w * tiles_h;
+  if (blocks > 0x7fffffff) return (int)hipErrorInvalidValue;
+  const int PH = a.d.stride * (CR_TH - 1) + a.d.KH, PW = a.d.stride * (CR_TW - 1) + 8;
+  const size_t lds = (size_t)PH * PW * 4 + (size_t)a.w.n_tiles * TILE_M * 16;  // at most 63 KiB
+  const dim3 grid((unsigned)blocks), block(256);
+  switch (a.d.KH) {
+    case 3: hipLaunchKernelGGL(conv_rows_kernel<3>, grid, block, lds, s, a, tiles_w, tiles_h); break;
+    case 5: hipLaunchKernelGGL(conv_rows_kernel<5>, grid, block, lds, s, a, tiles_w, tiles_h); break;
+    case 7: hipLaunchKernelGGL(conv_rows_kernel<7>, grid, block, lds, s, a, tiles_w, tiles_h); break;
+    default: hipLaunchKernelGGL(conv_rows_kernel<0>, grid, block, lds, s, a, tiles_w, tiles_h); break;
+  }
+  return (int)hipGetLastError();
+}
+
 int launch_gemm(const GemmArgs& a, void* stream) {
   hipStream_t s = (hipStream_t)stream;
   if (a.N <= 0) return 0;
+  if (conv_rows_applies(a)) return launch_conv_rows(a, s);
   if (!a.conv && skinny_applies(a)) return a.N <= 32 ? launch_skinny_t<1>(a, s) : launch_skinny_t<2>(a, s);
   {
     GemmArgs pa;
@@ -1277,7 +1416,7 @@ int launch_gemm(const GemmArgs& a, void* stream) {
 // ---------------------------------------------------------------- explicit im2col
 //
 // Fallback for layers whose channel count is not a multiple of 16: writes the lowered matrix
-// [N][Kpad] in the K order the weights are stored in, (kh, kw) outer and channel inner.
+// [N][Kpad] in the K order the weights are stored in (either KLayout).
 // One thread per output byte.
 template <int ACT_BITS>
 __global__ __launch_bounds__(256) void im2col_kernel(Im2colArgs a) {
@@ -1292,9 +1431,20 @@ __global__ __launch_bounds__(256) void im2col_kernel(Im2colArgs a) {
   const int oh = rem / a.OW, ow = rem - oh * a.OW;
   const uint8_t* X = (const uint8_t*)a.X;
   auto code = [&](int64_t kk) -> uint32_t {
-    if (kk >= a.K) return 0u;
-    const int tap = (int)(kk / a.d.C), cc = (int)(kk - (int64_t)tap * a.d.C);
-    const int kh = tap / a.d.KW, kw = tap - kh * a.d.KW;
+    int kh, kw, cc;
+    if (a.k_layout == K_FILTER_ROWS) {
+      kh = (int)(kk / KSTEP);
+      const int r = (int)(kk - (int64_t)kh * KSTEP);
+      kw = r / 4;
+      cc = r - 4 * kw;
+      if (kh >= a.d.KH || kw >= a.d.KW || cc >= a.d.C) return 0u;  // the weight there is zero
+    } else {
+      if (kk >= a.K) return 0u;
+      const int tap = (int)(kk / a.d.C);
+      cc = (int)(kk - (int64_t)tap * a.d.C);
+      kh = tap / a.d.KW;
+      kw = tap - kh * a.d.KW;
+    }
     const int ih = oh * a.d.stride - a.d.pad + kh, iw = ow * a.d.stride - a.d.pad + kw;
     if (ih < 0 || ih >= a.d.H || iw < 0 || iw >= a.d.W) return (uint32_t)a.zero_point & (ACT_BITS == 4 ? 15u : 255u);
     const int64_t pix = ((int64_t)b * a.d.H + ih) * a.d.W + iw;

@@ -148,11 +148,17 @@ rmsmp_status pack_host(const float* W, int64_t M, int64_t K, const uint8_t* sche
   hp->K = K;
   hp->C = C;
   hp->taps = taps;
-  hp->Kpad = (K + KPAD_UNIT - 1) / KPAD_UNIT * KPAD_UNIT;
+  // filter-row layout for small-channel square filters (see KLayout)
+  int64_t kw_side = 0;
+  while (kw_side * kw_side < taps) ++kw_side;
+  const bool rows_layout = taps > 1 && C <= 4 && kw_side * kw_side == taps && kw_side <= 8;
+  hp->k_layout = rows_layout ? K_FILTER_ROWS : K_TAP_CHANNEL;
+  const int64_t Kint = rows_layout ? kw_side * KSTEP : K;
+  hp->Kpad = (Kint + KPAD_UNIT - 1) / KPAD_UNIT * KPAD_UNIT;
   hp->nks = hp->Kpad / KSTEP;
 
-  // internal K order: (tap, channel position) -> original (channel, tap)
-  hp->kmap.resize((size_t)K);
+  // internal K order -> original (channel, tap) index; -1 where the internal axis is padding
+  hp->kmap.assign((size_t)hp->Kpad, -1);
   {
     std::vector<char> seen((size_t)C, 0);
     for (int64_t j = 0; j < C; ++j) {
@@ -162,7 +168,10 @@ rmsmp_status pack_host(const float* W, int64_t M, int64_t K, const uint8_t* sche
         return RMSMP_EINVAL;
       }
       seen[(size_t)c] = 1;
-      for (int64_t t = 0; t < taps; ++t) hp->kmap[(size_t)(t * C + j)] = (int32_t)(c * taps + t);
+      for (int64_t t = 0; t < taps; ++t) {
+        const int64_t kint = rows_layout ? (t / kw_side) * KSTEP + (t % kw_side) * 4 + j : t * C + j;
+        hp->kmap[(size_t)kint] = (int32_t)(c * taps + t);
+      }
     }
   }
 
@@ -307,7 +316,7 @@ rmsmp_status pack_host(const float* W, int64_t M, int64_t K, const uint8_t* sche
           int8_t v[16];
           for (int e = 0; e < 16; ++e) {
             const int64_t kk = ks * KSTEP + kb * 16 + e;
-            v[e] = kk < K ? q[hp->kmap[(size_t)kk]] : (int8_t)0;
+            v[e] = hp->kmap[(size_t)kk] >= 0 ? q[hp->kmap[(size_t)kk]] : (int8_t)0;
           }
           if (td.kind == TILE_I8) {
             uint8_t* dst = hp->blob.data() + td.blob_off + (ks * LANES + lane) * 16;
@@ -377,7 +386,7 @@ void unpack_host(const HostPacked& hp, const uint8_t* blob, int8_t* wint) {
           }
           for (int e = 0; e < 16; ++e) {
             const int64_t kk = ks * KSTEP + kb * 16 + e;
-            if (kk < K) wint[orig * K + hp.kmap[(size_t)kk]] = v[e];
+            if (hp.kmap[(size_t)kk] >= 0) wint[orig * K + hp.kmap[(size_t)kk]] = v[e];
           }
         }
     }

@@ -23,6 +23,17 @@ constexpr int LANES = 64;
 // lanes 32..63 rows 16..31), so a lane can emit its 4-bit output codes as one 8-byte store.
 constexpr int tile_row_goff(int i) { return 16 * ((i / 4) % 2) + 4 * (i / 8) + i % 4; }
 
+// Order of the internal (stored) K axis.
+enum KLayout : int32_t {
+  // (tap, input-channel position): K = taps * C, padded at the end.  Plain GEMMs have one tap.
+  K_TAP_CHANNEL = 0,
+  // Layers with at most four input channels and a square KW x KW filter, KW <= 8 (a network's
+  // first layer): one K step per filter row, element (kh, kw, c) at kh*32 + kw*4 + c, zero
+  // weights where kw >= KW or c >= C.  A filter row of an NHWC image whose pixels are padded to
+  // four bytes is then one aligned 32-byte run, and no im2col matrix has to be built.
+  K_FILTER_ROWS = 1
+};
+
 // How a tile's codes are stored and decoded in registers.
 enum TileKind : int32_t {
   TILE_NIB_SHIFT = 0,  // 4-bit two's-complement codes; decode = mask/shift, yields 16*q
@@ -45,13 +56,14 @@ constexpr int kSlot[16] = {0, 2, 4, 6, 1, 3, 5, 7, 8, 10, 12, 14, 9, 11, 13, 15}
 struct HostPacked {
   int64_t M = 0, K = 0, C = 0;
   int32_t taps = 1;
+  int32_t k_layout = 0;            // KLayout of the internal K axis
   int64_t Kpad = 0, nks = 0;
   int64_t counts[3] = {0, 0, 0};
   std::vector<int32_t> perm;       // [M] grouped position -> original row
   std::vector<float> rowscale;     // [M] original order
   std::vector<int32_t> rowsum;     // [M] original order
   std::vector<uint8_t> scheme;     // [M] original order
-  std::vector<int32_t> kmap;       // [K] internal k -> original k
+  std::vector<int32_t> kmap;       // [Kpad] internal k -> original k, -1 = zero padding
   std::vector<TileDesc> tiles;
   // tables indexed by padded grouped row p = tile*TILE_M + grouped offset
   std::vector<float> p_rowscale;
@@ -80,6 +92,7 @@ struct DevicePacked {
   const uint32_t* p_lut = nullptr;
   int32_t n_tiles = 0;
   int32_t nks = 0;
+  int32_t k_layout = 0;  // KLayout
   // Tiles are ordered by class (TileKind 0, 1, 2) and all tiles of a class have the same size,
   // so a kernel finds a tile's class, blob offset and live row count from these six numbers
   // without touching memory.
@@ -108,12 +121,13 @@ struct GemmArgs {
 
 struct Im2colArgs {
   const void* X = nullptr;
-  void* cols = nullptr;  // [N][Kpad/2] (4-bit) or [N][Kpad] (8-bit), internal K order (tap, c)
+  void* cols = nullptr;  // [N][Kpad/2] (4-bit) or [N][Kpad] (8-bit), internal K order
   rmsmp_conv_desc d{};
   int32_t OH = 0, OW = 0;
   int64_t N = 0, K = 0, Kpad = 0;
   int32_t act_bits = 4;
   int32_t zero_point = 0;
+  int32_t k_layout = 0;  // KLayout of the columns to produce
 };
 
 // Kernel launchers (kernels.hip).  Return hipError_t as int.

@@ -277,6 +277,35 @@ def test_conv_first_layer_int8_activations(rm, oracle):
     run_conv(rm, oracle, (2, 3, 32, 32, 7, 7, 2, 3), 64, (0, 0, 100), act_bits=8, relu=True, requant=True)
 
 
+@pytest.mark.parametrize("geom", [(2, 3, 32, 32, 7, 7, 2, 3), (3, 3, 21, 19, 7, 7, 2, 3), (1, 4, 20, 33, 3, 3, 1, 1),
+                                  (2, 1, 17, 17, 5, 5, 3, 2), (1, 2, 9, 40, 8, 8, 1, 0), (2, 3, 16, 16, 3, 3, 2, 0)])
+@pytest.mark.parametrize("M,ratio", [(64, (0, 0, 100)), (40, (35, 60, 5)), (160, (35, 60, 5))])
+def test_conv_small_channel_int8_direct(rm, oracle, geom, M, ratio):
+    """8-bit layers with at most four input channels run without an im2col matrix: output tiles that
+    are ragged in both directions, strides 1..3, filters 3..8 wide, more than four weight tiles,
+    every row class, a zero point."""
+    z = (sum(geom) + M) % 7 - 3
+    assert run_conv(rm, oracle, geom, M, ratio, act_bits=8, z=z, relu=True, requant=True, seed=5) == 0
+
+
+@pytest.mark.parametrize("geom", [(2, 4, 9, 9, 3, 3, 1, 1), (1, 2, 8, 7, 3, 3, 2, 1)])
+def test_conv_small_channel_u4_through_workspace(rm, oracle, geom):
+    """The same storage layout with 4-bit activations goes through the materialised im2col matrix."""
+    ws = run_conv(rm, oracle, geom, 40, (35, 60, 5), z=3, relu=True, requant=True)
+    assert ws > 0
+
+
+def test_small_channel_weights_are_conv_only(rm):
+    rng = np.random.default_rng(3)
+    p = rm.rmsmp_pack_weights(si.weights_rowscaled(rng, 8, 27), np.zeros(8, np.uint8), taps=9)
+    X = torch.zeros((4, 27), dtype=torch.int8, device=DEV)
+    Y = torch.empty((8, 4), dtype=torch.int32, device=DEV)
+    with pytest.raises(rm.RmsmpError) as e:
+        rm.rmsmp_gemm(p, X, 4, rm.make_epilogue(act_bits=8), Y)
+    assert e.value.code == 5
+    p.free()
+
+
 def test_chained_layers_through_grouped_order(rm, oracle):
     """Layer 1 writes 4-bit output in grouped row order; layer 2 is packed with in_perm = that
     order and must give what the oracle gives on the original channel order."""

@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol(rm):
 
 
 @pytest.mark.parametrize("M,K,taps", [(64, 576, 1), (64, 576, 9), (37, 130, 1), (256, 2304, 9), (17, 64, 1),
-                                       (48, 147, 49)])
+                                       (48, 147, 49), (40, 36, 9), (40, 18, 9), (16, 25, 25), (33, 256, 64)])
 def test_pack_roundtrip_matches_oracle_levels(rm, oracle, M, K, taps):
     rng = np.random.default_rng(M * 1000 + K)
     W = si.weights_rowscaled(rng, M, K)
@@ -104,6 +104,21 @@ def test_grouping_by_scheme_in_whole_tiles(rm, oracle):
             i8_start = first_f8 - first_f8 % 32
             assert np.all(s[:i8_start] != 2)
         assert np.bincount(scheme, minlength=3).tolist() == list(counts)
+
+
+def test_in_perm_with_filter_row_layout(rm, oracle):
+    """Layers with at most four input channels are stored one filter row per K step; the channel
+    permutation must act the same way there."""
+    rng = np.random.default_rng(12)
+    M, C, taps = 10, 4, 9
+    W = si.weights_rowscaled(rng, M, C * taps)
+    scheme = si.scheme_permutation(rng, oracle.ratio_counts(M, 35, 60, 5))
+    perm = np.array([2, 0, 3, 1], np.int32)
+    a = rm.rmsmp_pack_roundtrip_host(W, scheme, taps=taps)
+    b = rm.rmsmp_pack_roundtrip_host(W, scheme, taps=taps, in_perm=perm)
+    # the permutation changes where codes are stored, not which code belongs to which (c, kh, kw)
+    assert np.array_equal(a["wint"], b["wint"])
+    assert np.array_equal(a["wint"].astype(np.int32), oracle.quantize_rows(W, scheme)["wint"])
 
 
 def test_in_perm_reorders_input_channels(rm, oracle):
