@@ -819,7 +819,7 @@ __device__ __forceinline__ void patch_prologue(const GemmArgs& a, const PatchGeo
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wt = wave & 1;
   const int kq = wave >> 1;
-  const int H = a.d.H, W = a.d.W, pad = a.d.pad;
+  const int H = a.d.H, W = a.d.W, pad = a.d.pad, S = a.d.stride;
   const int hw_out = a.OH * a.OW;
   const int row_stride = g.row_stride, patch_rows = g.patch_rows;
   ps.meta = smem_raw + PHASE_LDS_BYTES;
@@ -836,7 +836,7 @@ __device__ __forceinline__ void patch_prologue(const GemmArgs& a, const PatchGeo
     const int rem = n - b * hw_out;
     oh = fast_div(rem, g.magic_ow);
     ow = rem - oh * a.OW;
-    return (b * H + (oh - pad)) * W + (ow - pad);
+    return (b * H + (oh * S - pad)) * W + (ow * S - pad);
   };
   int toh, tow;
   int f_lo = base_index(ps.n0, toh, tow);
@@ -895,8 +895,8 @@ __device__ __forceinline__ void patch_prologue(const GemmArgs& a, const PatchGeo
     const bool n_ok = n < (int)a.N;
     int oh = 0, ow = 0;
     const int f0 = base_index(n_ok ? n : ps.n0, oh, ow);
-    const int kw_lo = max(0, pad - ow), kw_hi = min(KW - 1, W - 1 + pad - ow);
-    const int kh_lo = max(0, pad - oh), kh_hi = min(KH - 1, H - 1 + pad - oh);
+    const int kw_lo = max(0, pad - ow * S), kw_hi = min(KW - 1, W - 1 + pad - ow * S);
+    const int kh_lo = max(0, pad - oh * S), kh_hi = min(KH - 1, H - 1 + pad - oh * S);
     const uint32_t wbits = kw_hi >= kw_lo ? ((2u << kw_hi) - (1u << kw_lo)) : 0u;  // bits kw_lo..kw_hi
     uint32_t m = 0;
 #pragma unroll
@@ -1022,17 +1022,22 @@ static bool patch_kernel_applies(const GemmArgs& a0, GemmArgs* pa, PatchGeom* g,
     a.d = rmsmp_conv_desc{(int32_t)a.N, (int32_t)a.K, 1, 1, 1, 1, 1, 0};
     a.OH = a.OW = 1;
   }
-  if (a.d.stride != 1) return false;
   const int taps = a.d.KH * a.d.KW;
   if (!(taps == 1 || (a.d.KH == 3 && a.d.KW == 3))) return false;
+  // a strided 1x1 layer would stage stride^2 times the pixels it uses: the general kernel gathers instead
+  if (taps == 1 && a.d.stride > 1) return false;
   if (a.d.C % KSTEP != 0 || !patch_cpt_supported(taps, a.d.C / KSTEP)) return false;
   if (a.w.nks != taps * (a.d.C / KSTEP)) return false;
-  // the flattened input index of a tile's pixels must grow with the pixel number
-  if (a.OH > a.d.H || a.OW > a.d.W) return false;
+  // The flattened input index of tap (0,0) must grow with the output pixel number, also across
+  // output rows and images, so that a tile's pixels lie in one contiguous run of the input.
+  const int64_t S = a.d.stride;
+  const int64_t row_extra = S * ((int64_t)a.d.W - a.OW);                 // extra advance at an output-row boundary
+  const int64_t img_extra = (int64_t)a.d.W * ((int64_t)a.d.H - S * a.OH);  // and, on top, at an image boundary
+  if (row_extra < 0 || row_extra + img_extra < 0) return false;
   // widest run of flattened input pixels any 128-pixel tile touches
-  const int64_t span = (int64_t)PT_BN + (int64_t)(a.d.KH - 1) * a.d.W + (a.d.KW - 1)
-                       + (int64_t)(a.d.H - a.OH) * a.d.W * ((PT_BN + a.OH * a.OW - 1) / (a.OH * a.OW) + 1)
-                       + (int64_t)(a.d.W - a.OW) * ((PT_BN + a.OW - 1) / a.OW + 1);
+  const int64_t rows_crossed = (PT_BN + a.OW - 1) / a.OW + 1, imgs_crossed = (PT_BN + (int64_t)a.OH * a.OW - 1) / ((int64_t)a.OH * a.OW) + 1;
+  const int64_t span = (int64_t)(PT_BN - 1) * S + 1 + (int64_t)(a.d.KH - 1) * a.d.W + (a.d.KW - 1) + rows_crossed * row_extra +
+                       imgs_crossed * (img_extra > 0 ? img_extra : 0);
   // 32-bit pixel arithmetic and exact one-multiply division in the kernel
   const int64_t hw = (int64_t)a.OH * a.OW, in_px = (int64_t)a.d.B * a.d.H * a.d.W;
   if ((a.N + PT_BN) * hw >= ((int64_t)1 << 32) || in_px * (a.d.C / 2) >= ((int64_t)1 << 40)) return false;

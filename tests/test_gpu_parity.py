@@ -234,6 +234,16 @@ def test_conv_stride1_lds_patch_kernel(rm, oracle, geom, M):
     run_conv(rm, oracle, geom, M, (100, 0, 0), z=0, seed=4)
 
 
+@pytest.mark.parametrize("geom", [(2, 64, 12, 12, 3, 3, 2, 1), (3, 128, 16, 14, 3, 3, 2, 1), (1, 64, 30, 30, 1, 1, 2, 0),
+                                  (2, 256, 14, 14, 3, 3, 2, 1), (2, 64, 9, 9, 3, 3, 3, 0), (40, 64, 4, 4, 1, 1, 2, 0)])
+@pytest.mark.parametrize("M", [64, 90])
+def test_conv_strided_lds_patch_kernel(rm, oracle, geom, M):
+    """Strided layers through the LDS-resident kernel (3x3 and 1x1, stride 2 and 3): the patch of a
+    pixel tile then spans several input rows and images with gaps the kernel never reads."""
+    z = (sum(geom) + M) % 16
+    assert run_conv(rm, oracle, geom, M, (35, 60, 5), z=z, relu=True, requant=True, seed=6) == 0
+
+
 def test_config1_resnet_layer_full_size(rm, oracle):
     """configs[1] at its benchmark size, every output compared: batch 32, 256->256, 14x14, 3x3 s1 p1
     (GEMM 256 x 2304 x 6272), 60:35:5, ReLU + 4-bit requant."""
