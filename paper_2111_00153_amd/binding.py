@@ -9,6 +9,9 @@ import ctypes
 import os
 
 import numpy as np
+# torch ships its own copy of the HIP runtime: it has to be in the process before the library is
+# loaded, so that both resolve to that one copy (two runtimes in one process do not see the GPU)
+import torch  # noqa: F401
 
 from . import build as _build
 
@@ -76,7 +79,6 @@ def _dev(t):
 
 def _stream(stream):
     if stream is None:
-        import torch
         stream = torch.cuda.current_stream()
     return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
 

@@ -34,7 +34,7 @@ extern __shared__ __attribute__((aligned(16))) uint8_t phase_smem[];
   do {                                                                                                   \
     if (g_phase_buf && (threadIdx.x & 63) == 0)                                                          \
       for (int i_ = 0; i_ < 16; ++i_)                                                                    \
-        g_phase_buf[((blockIdx.y * gridDim.x + blockIdx.x) * 8 + (threadIdx.x >> 6)) * 16 + i_] =        \
+        g_phase_buf[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + i_] =                                  \
             ((unsigned long long*)phase_smem)[(threadIdx.x >> 6) * 16 + i_];                             \
   } while (0)
 #else
@@ -557,6 +557,7 @@ constexpr int PT_KSPLIT = 2;                    // waves sharing one output bloc
 constexpr int PT_XCH_BYTES = 4 * 2 * 16 * LANES * 4;  // partial-sum exchange buffer in LDS
 
 struct PatchGeom {
+  int gx, gy;         // pixel tiles, work-groups per pixel tile (the launch grid is one-dimensional)
   int row_stride;     // LDS bytes per patch pixel (C + 16)
   int patch_rows;     // pixels staged per work-group
   uint32_t magic_hw;  // ceil(2^32 / (OH*OW)), 0 when OH*OW == 1
@@ -827,7 +828,6 @@ __device__ __forceinline__ void patch_prologue(const GemmArgs& a, const PatchGeo
   // the exchange buffer lies over it; with several pairs the patch has to survive
   ps.xch = ps.meta + PT_META_BYTES;
   ps.patch = MULTI ? ps.xch + PT_XCH_BYTES : ps.xch;
-  ps.n0 = blockIdx.x * PT_BN;
   uint8_t* const smem = ps.patch;
 
   // flattened input index of tap (0,0) for output pixel n (may be negative / out of image)
@@ -961,13 +961,22 @@ __device__ __forceinline__ int patch_body(const GemmArgs& a, const EpArgs& ea, c
 template <int TAPS, int CPT, bool MULTI>
 __device__ __forceinline__ void patch_kernel_impl(const GemmArgs& a, const PatchGeom& g, int pairs_per_wg) {
   RMSMP_PHASE(0);
+  // Work-group id -> (pixel tile bx, row block by).  Consecutive ids go to different XCDs, each
+  // with its own L2, so the gy work-groups that read the same input patch get ids that are equal
+  // modulo 8 and follow each other on that XCD: the patch comes out of memory once, not gy
+  // times.  The grid is padded to a multiple of 8 pixel tiles; the extra work-groups leave.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int by = slot % g.gy;
+  const int bx = (slot / g.gy) * 8 + xcd;
+  if (bx >= g.gx) return;
   EpArgs ea = pin_epilogue_args(a);
   ea.stamps = PHASE_LDS_BYTES != 0;
   RMSMP_PHASE(14);
   const int n_pairs = (a.w.n_tiles + 1) / 2;
-  const int pair_lo = MULTI ? blockIdx.y * pairs_per_wg : blockIdx.y;
+  const int pair_lo = MULTI ? by * pairs_per_wg : by;
   const int pair_hi = MULTI ? min(pair_lo + pairs_per_wg, n_pairs) : pair_lo + 1;
   PatchState ps;
+  ps.n0 = bx * PT_BN;
   PairLoads pl;
   pl.T0 = pl.T1 = make_uint4(0, 0, 0, 0);
   int pi = pair_lo;
@@ -1065,7 +1074,10 @@ static bool patch_kernel_applies(const GemmArgs& a0, GemmArgs* pa, PatchGeom* g,
   g->magic_ow = div_magic(a.OW);
   *lds_bytes = ppw == 1 ? lds_single : lds_multi;
   *pairs_per_wg = (int)ppw;
-  *grid = dim3((unsigned)gx, (unsigned)gy, 1);
+  if ((gx + 7) / 8 * 8 * gy > 0x7fffffff) return false;
+  g->gx = (int)gx;
+  g->gy = gy;
+  *grid = dim3((unsigned)((gx + 7) / 8 * 8 * gy), 1, 1);
   *pa = a;
   return true;
 }
