@@ -8,6 +8,7 @@
 // (Section 4.1); on CDNA4 the matrix cores take int8 either way, so the scheme only decides
 // how a tile is decoded.  Accumulation is int32 and exact.
 #include <hip/hip_runtime.h>
+#include <type_traits>
 
 #include "rmsmp_internal.h"
 
@@ -545,16 +546,20 @@ static int launch_general(const GemmArgs& a, hipStream_t s) {
 // latency is paid.  The K loop is fully unrolled straight-line code: with branches in it the
 // compiler can no longer count outstanding loads and waits for all of them at every step, and a
 // rolled loop makes it copy the ring registers at the back edge, which drains the ring as well.
-constexpr int PT_BN = 128;
 constexpr int PT_THREADS = 256;
+// K split KS: how many waves share one 64x64 output block, each taking every KS-th K step.
+// KS = 2: work-group = 128 pixels (two blocks side by side); KS = 4: 64 pixels, for grids too
+// small to put two work-groups on a compute unit otherwise (a wave issues in order and cannot
+// hide its own decode behind its own MFMAs; a second wave on the SIMD can).
+constexpr int pt_bn(int ks) { return 64 * (4 / ks); }
+// bytes of the partial-sum exchange buffer: every wave parks the quarters of its block it does not finish
+constexpr int pt_xch_bytes(int ks) { return 4 * (4 - 4 / ks) * 16 * LANES * 4; }
 constexpr int PT_PATCH_UNROLL = 6;              // 16-byte patch pieces in flight per thread
 constexpr int PT_META_BYTES = 2 * TILE_M * 16;  // row metadata of the work-group's 64 rows, kept at the start of LDS
 #ifndef RMSMP_PT_RING
 #define RMSMP_PT_RING 4
 #endif
 constexpr int PT_RING = RMSMP_PT_RING;          // K steps of packed weights in flight per wave and tile
-constexpr int PT_KSPLIT = 2;                    // waves sharing one output block
-constexpr int PT_XCH_BYTES = 4 * 2 * 16 * LANES * 4;  // partial-sum exchange buffer in LDS
 
 struct PatchGeom {
   int gx, gy;         // pixel tiles, work-groups per pixel tile (the launch grid is one-dimensional)
@@ -592,31 +597,31 @@ struct PairLoads {
   int4 meta_row;
 };
 
-template <int NSTEP>
+template <int NSTEP, int KS>
 __device__ __forceinline__ void issue_ring(const uint8_t* wb, int kind, int lane, uint4 (&ring)[PT_RING]) {
   if (kind == TILE_I8) {
 #pragma unroll
     for (int u = 0; u < PT_RING; ++u)
-      if (u < NSTEP) ring[u] = *(const uint4*)(wb + (int64_t)u * PT_KSPLIT * (LANES * 16) + (uint32_t)lane * 16);
+      if (u < NSTEP) ring[u] = *(const uint4*)(wb + (int64_t)u * KS * (LANES * 16) + (uint32_t)lane * 16);
   } else {
 #pragma unroll
     for (int u = 0; u < PT_RING; ++u)
       if (u < NSTEP) {
-        const uint2 w = *(const uint2*)(wb + (int64_t)u * PT_KSPLIT * (LANES * 8) + (uint32_t)lane * 8);
+        const uint2 w = *(const uint2*)(wb + (int64_t)u * KS * (LANES * 8) + (uint32_t)lane * 8);
         ring[u].x = w.x;
         ring[u].y = w.y;
       }
   }
 }
 
-template <int NSTEP>
+template <int NSTEP, int KS>
 __device__ __forceinline__ void issue_pair_loads(const GemmArgs& a, int mt0, int mt1, const TileRef& tr0, const TileRef& tr1,
                                                  PairLoads& pl) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int kq = __builtin_amdgcn_readfirstlane(tid >> 6) >> 1;
-  issue_ring<NSTEP>(a.w.blob + tr0.blob_off + kq * (LANES * (tr0.kind == TILE_I8 ? 16 : 8)), tr0.kind, lane, pl.ring0);
-  issue_ring<NSTEP>(a.w.blob + tr1.blob_off + kq * (LANES * (tr1.kind == TILE_I8 ? 16 : 8)), tr1.kind, lane, pl.ring1);
+  const int kq = __builtin_amdgcn_readfirstlane(tid >> 6) / (4 / KS);
+  issue_ring<NSTEP, KS>(a.w.blob + tr0.blob_off + kq * (LANES * (tr0.kind == TILE_I8 ? 16 : 8)), tr0.kind, lane, pl.ring0);
+  issue_ring<NSTEP, KS>(a.w.blob + tr1.blob_off + kq * (LANES * (tr1.kind == TILE_I8 ? 16 : 8)), tr1.kind, lane, pl.ring1);
   if (tr0.kind == TILE_NIB_LUT) pl.T0 = *(const uint4*)(a.w.p_lut + ((int64_t)mt0 * TILE_M + tile_row_goff(lane & 31)) * 4);
   if (tr1.kind == TILE_NIB_LUT) pl.T1 = *(const uint4*)(a.w.p_lut + ((int64_t)mt1 * TILE_M + tile_row_goff(lane & 31)) * 4);
   // threads 0..31 fetch tile 0's rows, 32..63 tile 1's
@@ -645,20 +650,21 @@ struct NextPair {
 // One tile pair: weight rings, K loop, partial-sum exchange, epilogue.  KIND0 / KIND1 are the
 // storage classes of the two weight tiles (template parameters so that the K loop has no
 // branches).
-template <int TAPS, int CPT, int KIND0, int KIND1, bool MULTI>
+template <int TAPS, int CPT, int KIND0, int KIND1, bool MULTI, int KS>
 __device__ __forceinline__ void patch_pair(const GemmArgs& a, const EpArgs& ea, const PatchGeom& g, const PatchState& ps,
                                            PairLoads& pl, const TileRef& tr0, const TileRef& tr1, bool two,
                                            const NextPair& next) {
   constexpr int KW = TAPS == 9 ? 3 : 1;
   constexpr int NKS = TAPS * CPT;
-  constexpr int NSTEP = NKS / PT_KSPLIT;  // K steps per wave (CPT is even)
-  constexpr int SPT = CPT / PT_KSPLIT;    // of which per tap
-  static_assert(CPT % PT_KSPLIT == 0, "a tap must hold a whole number of K steps per wave");
+  constexpr int NSTEP = NKS / KS;  // K steps per wave
+  constexpr int SPT = CPT / KS;    // of which per tap
+  static_assert(CPT % KS == 0, "a tap must hold a whole number of K steps per wave");
+  constexpr int NWT = 4 / KS;      // 64-pixel blocks side by side in the work-group
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wt = wave & 1;   // which 64-pixel half of the work-group's 128 pixels
-  const int kq = wave >> 1;  // K steps kq, kq+2, ...
+  const int wt = wave % NWT;  // which 64-pixel block of the work-group
+  const int kq = wave / NWT;  // K steps kq, kq+KS, ...
   const int W = a.d.W;
   const int row_stride = g.row_stride;
   const uint8_t* smem = ps.patch;
@@ -704,8 +710,8 @@ __device__ __forceinline__ void patch_pair(const GemmArgs& a, const EpArgs& ea, 
     v4i av0 = decode_raw<KIND0>(raw_of<KIND0>(pl.ring0[0]), T0);
     v4i av1 = decode_raw<KIND1>(raw_of<KIND1>(pl.ring1[0]), T1);
     if (PT_RING < NSTEP) {
-      raw_into(pl.ring0[0], load_raw<KIND0>(wb0 + (int64_t)PT_RING * PT_KSPLIT * step0, wl0));
-      raw_into(pl.ring1[0], load_raw<KIND1>(wb1 + (int64_t)PT_RING * PT_KSPLIT * step1, wl1));
+      raw_into(pl.ring0[0], load_raw<KIND0>(wb0 + (int64_t)PT_RING * KS * step0, wl0));
+      raw_into(pl.ring1[0], load_raw<KIND1>(wb1 + (int64_t)PT_RING * KS * step1, wl1));
     }
     constexpr int NV0 = KIND0 == TILE_NIB_SHIFT ? 6 : KIND0 == TILE_NIB_LUT ? 22 : 0;
     constexpr int NV1 = KIND1 == TILE_NIB_SHIFT ? 6 : KIND1 == TILE_NIB_LUT ? 22 : 0;
@@ -718,15 +724,15 @@ __device__ __forceinline__ void patch_pair(const GemmArgs& a, const EpArgs& ea, 
         nav0 = decode_raw<KIND0>(raw_of<KIND0>(pl.ring0[u]), T0);
         nav1 = decode_raw<KIND1>(raw_of<KIND1>(pl.ring1[u]), T1);
         if (i + 1 + PT_RING < NSTEP) {
-          raw_into(pl.ring0[u], load_raw<KIND0>(wb0 + (int64_t)(i + 1 + PT_RING) * PT_KSPLIT * step0, wl0));
-          raw_into(pl.ring1[u], load_raw<KIND1>(wb1 + (int64_t)(i + 1 + PT_RING) * PT_KSPLIT * step1, wl1));
+          raw_into(pl.ring0[u], load_raw<KIND0>(wb0 + (int64_t)(i + 1 + PT_RING) * KS * step0, wl0));
+          raw_into(pl.ring1[u], load_raw<KIND1>(wb1 + (int64_t)(i + 1 + PT_RING) * KS * step1, wl1));
         }
         if ((i + 1) % SPT == 0) {
           cur0 = tap_base((i + 1) / SPT, 0);
           cur1 = tap_base((i + 1) / SPT, 1);
         }
-        nb0 = *(const v4i*)(smem + cur0 + ((i + 1) % SPT) * PT_KSPLIT * KSTEP);
-        nb1 = *(const v4i*)(smem + cur1 + ((i + 1) % SPT) * PT_KSPLIT * KSTEP);
+        nb0 = *(const v4i*)(smem + cur0 + ((i + 1) % SPT) * KS * KSTEP);
+        nb1 = *(const v4i*)(smem + cur1 + ((i + 1) % SPT) * KS * KSTEP);
       }
       acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av0, b0, acc[0][0], 0, 0, 0);
       acc[0][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av0, b1, acc[0][1], 0, 0, 0);
@@ -757,49 +763,82 @@ __device__ __forceinline__ void patch_pair(const GemmArgs& a, const EpArgs& ea, 
 
   RMSMP_PHASE(3);
   // ---- the rings are drained: start the next pair's reads now, behind the exchange and epilogue
-  if (MULTI && next.valid) issue_pair_loads<NSTEP>(a, next.mt0, next.mt1, next.tr0, next.tr1, pl);
-  // ---- add the two partial sums of a block.  Wave kq finishes weight tile kq of the block
-  // (both pixel blocks) and hands the other tile's partial sums to its partner.  The two roles
-  // are two copies of the code under a wave-uniform branch, so that which accumulators are
-  // given and which are kept is static (selecting them per element costs 64 instructions).
+  if (MULTI && next.valid) issue_pair_loads<NSTEP, KS>(a, next.mt0, next.mt1, next.tr0, next.tr1, pl);
+  // ---- add the KS partial sums of a block.  The block's four quarters (weight tile t, pixel
+  // block j: quarter 2t + j) are shared out among the KS waves: wave kq finishes quarters
+  // kq*OWN .. kq*OWN+OWN-1 and parks the others in LDS for their owners.  The roles are KS copies
+  // of the code under a wave-uniform branch, so that which accumulators are given and which are
+  // kept is static (selecting them per element would cost 64 instructions).
+  constexpr int OWN = 4 / KS;  // quarters a wave finishes: 2 (one tile, both pixel blocks) or 1
   if (!MULTI) __syncthreads();  // the exchange buffer overlays the patch: every wave is done reading it
-  v16i mine[2];
-  auto exchange = [&](const v16i (&give)[2], const v16i (&keep)[2]) {
-    int* dst = (int*)ps.xch + wave * (2 * 16 * LANES);  // slot [giver wave][pixel block]
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
+  v16i mine[OWN];
+  auto exchange = [&](auto kq_tag) {
+    constexpr int KQ = decltype(kq_tag)::value;
+    // slot [wave of the block][given quarter, in increasing order], 16 registers x 64 lanes each
+    int* const blk = (int*)ps.xch + wt * (KS * (4 - OWN) * 16 * LANES);
+    {
+      int* dst = blk + KQ * ((4 - OWN) * 16 * LANES);
+      int gi = 0;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        v4i gq;
+        if (q / OWN == KQ) continue;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) gq[e] = give[j][4 * q + e];
-        *(v4i*)(dst + j * (16 * LANES) + q * (4 * LANES) + lane * 4) = gq;
+        for (int c = 0; c < 4; ++c) {
+          v4i gq;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) gq[e] = acc[q >> 1][q & 1][4 * c + e];
+          *(v4i*)(dst + gi * (16 * LANES) + c * (4 * LANES) + lane * 4) = gq;
+        }
+        ++gi;
       }
+    }
     __syncthreads();
     RMSMP_PHASE(4);
-    const int* src = (const int*)ps.xch + (wave ^ 2) * (2 * 16 * LANES);
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int o = 0; o < OWN; ++o) {
+      constexpr int q0 = KQ * OWN;
+      const int q = q0 + o;
+      mine[o] = acc[q >> 1][q & 1];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const v4i got = *(const v4i*)(src + j * (16 * LANES) + q * (4 * LANES) + lane * 4);
+      for (int gk = 0; gk < KS; ++gk) {
+        if (gk == KQ) continue;
+        // where giver gk put quarter q: its given quarters are all but its own, in order
+        const int gi = q < gk * OWN ? q : q - OWN;
+        const int* src = blk + gk * ((4 - OWN) * 16 * LANES) + gi * (16 * LANES);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) mine[j][4 * q + e] = keep[j][4 * q + e] + got[e];
+        for (int c = 0; c < 4; ++c) {
+          const v4i got = *(const v4i*)(src + c * (4 * LANES) + lane * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) mine[o][4 * c + e] += got[e];
+        }
       }
+    }
   };
   if (kq == 0)
-    exchange(acc[1], acc[0]);
-  else
-    exchange(acc[0], acc[1]);
-  if (!(kq == 1 && !two)) {
+    exchange(std::integral_constant<int, 0>{});
+  else if (kq == 1)
+    exchange(std::integral_constant<int, 1>{});
+  else if (KS == 4 && kq == 2)
+    exchange(std::integral_constant<int, KS == 4 ? 2 : 0>{});
+  else if (KS == 4)
+    exchange(std::integral_constant<int, KS == 4 ? 3 : 0>{});
+  // the quarters this wave finishes belong to one weight tile
+  const int my_tile = kq * OWN / 2;
+  if (!(my_tile == 1 && !two)) {
     RMSMP_PHASE(5);
     RowMetaLds rm;
-    rm.base = (const int*)__builtin_assume_aligned((const int*)ps.meta + kq * TILE_M + 16 * (lane >> 5), 64);
+    rm.base = (const int*)__builtin_assume_aligned((const int*)ps.meta + my_tile * TILE_M + 16 * (lane >> 5), 64);
     rm.rows = 2 * TILE_M;
-    const int n_rows = lane_rows(kq ? tr1.nvalid : tr0.nvalid, lane);
-    const int kind = kq ? KIND1 : KIND0;
-    const int64_t ncol[2] = {(int64_t)ps.n0 + 64 * wt + (lane & 31), (int64_t)ps.n0 + 64 * wt + 32 + (lane & 31)};
-    finish_tiles<2>(ea, kind, mine, rm, n_rows, ncol);
+    const int n_rows = lane_rows(my_tile ? tr1.nvalid : tr0.nvalid, lane);
+    const int kind = my_tile ? KIND1 : KIND0;
+    const int64_t col0 = (int64_t)ps.n0 + 64 * wt + (lane & 31);
+    if constexpr (OWN == 2) {
+      const int64_t ncol[2] = {col0, col0 + 32};
+      finish_tiles<2>(ea, kind, mine, rm, n_rows, ncol);
+    } else {
+      const int64_t ncol[1] = {col0 + 32 * (kq & 1)};
+      finish_tiles<1>(ea, kind, mine, rm, n_rows, ncol);
+    }
   }
   RMSMP_PHASE(6);
 }
@@ -807,7 +846,7 @@ __device__ __forceinline__ void patch_pair(const GemmArgs& a, const EpArgs& ea, 
 // Everything a work-group does once, whatever its tile pairs: stage the input patch in LDS,
 // work out each lane's LDS addresses, and (behind the first batch of patch reads) start the
 // reads of the first tile pair.
-template <int TAPS, int CPT, bool MULTI>
+template <int TAPS, int CPT, bool MULTI, int KS>
 __device__ __forceinline__ void patch_prologue(const GemmArgs& a, const PatchGeom& g, PatchState& ps, PairLoads& pl,
                                                int first_mt0, int first_mt1, const TileRef& first_tr0,
                                                const TileRef& first_tr1) {
@@ -818,8 +857,8 @@ __device__ __forceinline__ void patch_prologue(const GemmArgs& a, const PatchGeo
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wt = wave & 1;
-  const int kq = wave >> 1;
+  const int wt = wave % (4 / KS);
+  const int kq = wave / (4 / KS);
   const int H = a.d.H, W = a.d.W, pad = a.d.pad, S = a.d.stride;
   const int hw_out = a.OH * a.OW;
   const int row_stride = g.row_stride, patch_rows = g.patch_rows;
@@ -827,7 +866,7 @@ __device__ __forceinline__ void patch_prologue(const GemmArgs& a, const PatchGeo
   // a work-group with one tile pair is done with the patch when it exchanges partial sums, so
   // the exchange buffer lies over it; with several pairs the patch has to survive
   ps.xch = ps.meta + PT_META_BYTES;
-  ps.patch = MULTI ? ps.xch + PT_XCH_BYTES : ps.xch;
+  ps.patch = MULTI ? ps.xch + pt_xch_bytes(KS) : ps.xch;
   uint8_t* const smem = ps.patch;
 
   // flattened input index of tap (0,0) for output pixel n (may be negative / out of image)
@@ -842,7 +881,7 @@ __device__ __forceinline__ void patch_prologue(const GemmArgs& a, const PatchGeo
   int f_lo = base_index(ps.n0, toh, tow);
   if (f_lo < 0) f_lo = 0;
 
-  constexpr int NSTEP = TAPS * CPT / PT_KSPLIT;
+  constexpr int NSTEP = TAPS * CPT / KS;
 
   // ---- 1. the patch.  Pixels f_lo .. f_lo+patch_rows-1 are one contiguous byte range of X;
   // piece idx (32 channels, 16 bytes) sits at byte 16*idx of it and goes, decoded to int8, to LDS
@@ -871,7 +910,7 @@ __device__ __forceinline__ void patch_prologue(const GemmArgs& a, const PatchGeo
         pw[u] = *(const uint4*)(X + off);
       }
       // behind the first batch of patch reads: everything the first tile pair needs
-      if (base == 0) issue_pair_loads<NSTEP>(a, first_mt0, first_mt1, first_tr0, first_tr1, pl);
+      if (base == 0) issue_pair_loads<NSTEP, KS>(a, first_mt0, first_mt1, first_tr0, first_tr1, pl);
       RMSMP_PHASE(7);
 #pragma unroll
       for (int u = 0; u < PT_PATCH_UNROLL; ++u) {
@@ -914,13 +953,13 @@ __device__ __forceinline__ void patch_prologue(const GemmArgs& a, const PatchGeo
 // function from start to end, so that its instruction stream is one contiguous run of code: a
 // kernel starts with cold instruction caches too, and every jump to code not yet fetched costs
 // a memory round trip.
-template <int TAPS, int CPT, int KIND0, int KIND1, bool MULTI>
+template <int TAPS, int CPT, int KIND0, int KIND1, bool MULTI, int KS>
 __device__ __forceinline__ int patch_body(const GemmArgs& a, const EpArgs& ea, const PatchGeom& g, PatchState& ps,
                                           PairLoads& pl, bool first, int pi, int pair_hi) {
   const int tid = threadIdx.x;
   int mt0 = pi, mt1 = a.w.n_tiles - 1 - pi;
   TileRef tr0 = tile_ref(a.w, mt0), tr1 = tile_ref(a.w, mt1);
-  if (first) patch_prologue<TAPS, CPT, MULTI>(a, g, ps, pl, mt0, mt1, tr0, tr1);
+  if (first) patch_prologue<TAPS, CPT, MULTI, KS>(a, g, ps, pl, mt0, mt1, tr0, tr1);
 #pragma unroll 1
   for (;;) {
     NextPair next;
@@ -941,7 +980,7 @@ __device__ __forceinline__ int patch_body(const GemmArgs& a, const EpArgs& ea, c
       mf[4 * TILE_M] = pl.meta_row.z;
       mf[6 * TILE_M] = pl.meta_row.w;
     }
-    patch_pair<TAPS, CPT, KIND0, KIND1, MULTI>(a, ea, g, ps, pl, tr0, tr1, two, next);
+    patch_pair<TAPS, CPT, KIND0, KIND1, MULTI, KS>(a, ea, g, ps, pl, tr0, tr1, two, next);
     ++pi;
     if (!next.valid) break;
     mt0 = next.mt0;
@@ -958,7 +997,7 @@ __device__ __forceinline__ int patch_body(const GemmArgs& a, const EpArgs& ea, c
 // tile shadows it and is never stored).  Tiles are sorted by class, so kind0 <= kind1.
 // MULTI = false is the one-pair-per-work-group build: no pair loop and no prefetch of a next
 // pair, which keeps it within the register budget of two work-groups per compute unit.
-template <int TAPS, int CPT, bool MULTI>
+template <int TAPS, int CPT, bool MULTI, int KS>
 __device__ __forceinline__ void patch_kernel_impl(const GemmArgs& a, const PatchGeom& g, int pairs_per_wg) {
   RMSMP_PHASE(0);
   // Work-group id -> (pixel tile bx, row block by).  Consecutive ids go to different XCDs, each
@@ -976,7 +1015,7 @@ __device__ __forceinline__ void patch_kernel_impl(const GemmArgs& a, const Patch
   const int pair_lo = MULTI ? by * pairs_per_wg : by;
   const int pair_hi = MULTI ? min(pair_lo + pairs_per_wg, n_pairs) : pair_lo + 1;
   PatchState ps;
-  ps.n0 = bx * PT_BN;
+  ps.n0 = bx * pt_bn(KS);
   PairLoads pl;
   pl.T0 = pl.T1 = make_uint4(0, 0, 0, 0);
   int pi = pair_lo;
@@ -985,7 +1024,7 @@ __device__ __forceinline__ void patch_kernel_impl(const GemmArgs& a, const Patch
   while (pi < pair_hi) {
     const int k0 = tile_ref(a.w, pi).kind, k1 = tile_ref(a.w, a.w.n_tiles - 1 - pi).kind;
 #define RMSMP_BODY(K0, K1) \
-  if (k0 == K0 && k1 == K1) pi = patch_body<TAPS, CPT, K0, K1, MULTI>(a, ea, g, ps, pl, first, pi, pair_hi);
+  if (k0 == K0 && k1 == K1) pi = patch_body<TAPS, CPT, K0, K1, MULTI, KS>(a, ea, g, ps, pl, first, pi, pair_hi);
     RMSMP_BODY(TILE_NIB_SHIFT, TILE_NIB_SHIFT)
     else RMSMP_BODY(TILE_NIB_SHIFT, TILE_NIB_LUT)
     else RMSMP_BODY(TILE_NIB_SHIFT, TILE_I8)
@@ -1002,12 +1041,18 @@ __device__ __forceinline__ void patch_kernel_impl(const GemmArgs& a, const Patch
 
 template <int TAPS, int CPT>
 __global__ __launch_bounds__(PT_THREADS, 2) void conv_patch_kernel(GemmArgs a, PatchGeom g) {
-  patch_kernel_impl<TAPS, CPT, false>(a, g, 1);
+  patch_kernel_impl<TAPS, CPT, false, 2>(a, g, 1);
+}
+
+// The same with four waves per output block (64 pixels per work-group) for small grids.
+template <int TAPS, int CPT>
+__global__ __launch_bounds__(PT_THREADS, 2) void conv_patch_split4_kernel(GemmArgs a, PatchGeom g) {
+  patch_kernel_impl<TAPS, CPT, false, 4>(a, g, 1);
 }
 
 template <int TAPS, int CPT>
 __global__ __launch_bounds__(PT_THREADS) void conv_patch_multi_kernel(GemmArgs a, PatchGeom g, int pairs_per_wg) {
-  patch_kernel_impl<TAPS, CPT, true>(a, g, pairs_per_wg);
+  patch_kernel_impl<TAPS, CPT, true, 2>(a, g, pairs_per_wg);
 }
 
 static uint32_t div_magic(int64_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + (uint64_t)d - 1) / (uint64_t)d); }
@@ -1018,11 +1063,18 @@ static bool patch_cpt_supported(int taps, int cpt) {
   return cpt == 2 || cpt == 4 || cpt == 8 || cpt == 16 || cpt == 24;
 }
 
-// Geometry checks for the LDS-resident kernel.  When it applies, *pa is the argument block to
-// launch it with (a plain GEMM becomes a 1x1 convolution over N single-pixel images) and the
-// LDS layout and grid are filled in.
-static bool patch_kernel_applies(const GemmArgs& a0, GemmArgs* pa, PatchGeom* g, size_t* lds_bytes, dim3* grid,
-                                 int* pairs_per_wg) {
+// How the LDS-resident kernel is launched.
+struct PatchPlan {
+  GemmArgs a;  // the argument block (a plain GEMM becomes a 1x1 convolution over N single-pixel images)
+  PatchGeom g;
+  size_t lds = 0;
+  unsigned blocks = 0;
+  int ks = 2;            // K split
+  int pairs_per_wg = 1;  // > 1: the multi-pair kernel
+};
+
+// Geometry checks for the LDS-resident kernel; fills the plan when it applies.
+static bool patch_kernel_applies(const GemmArgs& a0, PatchPlan* plan) {
   if (a0.ep.act_bits != 4) return false;
   GemmArgs a = a0;
   if (!a.conv) {
@@ -1035,56 +1087,70 @@ static bool patch_kernel_applies(const GemmArgs& a0, GemmArgs* pa, PatchGeom* g,
   if (!(taps == 1 || (a.d.KH == 3 && a.d.KW == 3))) return false;
   // a strided 1x1 layer would stage stride^2 times the pixels it uses: the general kernel gathers instead
   if (taps == 1 && a.d.stride > 1) return false;
-  if (a.d.C % KSTEP != 0 || !patch_cpt_supported(taps, a.d.C / KSTEP)) return false;
-  if (a.w.nks != taps * (a.d.C / KSTEP)) return false;
+  const int cpt = a.d.C / KSTEP;
+  if (a.d.C % KSTEP != 0 || !patch_cpt_supported(taps, cpt)) return false;
+  if (a.w.nks != taps * cpt) return false;
   // The flattened input index of tap (0,0) must grow with the output pixel number, also across
   // output rows and images, so that a tile's pixels lie in one contiguous run of the input.
   const int64_t S = a.d.stride;
-  const int64_t row_extra = S * ((int64_t)a.d.W - a.OW);                 // extra advance at an output-row boundary
+  const int64_t row_extra = S * ((int64_t)a.d.W - a.OW);                   // extra advance at an output-row boundary
   const int64_t img_extra = (int64_t)a.d.W * ((int64_t)a.d.H - S * a.OH);  // and, on top, at an image boundary
   if (row_extra < 0 || row_extra + img_extra < 0) return false;
-  // widest run of flattened input pixels any 128-pixel tile touches
-  const int64_t rows_crossed = (PT_BN + a.OW - 1) / a.OW + 1, imgs_crossed = (PT_BN + (int64_t)a.OH * a.OW - 1) / ((int64_t)a.OH * a.OW) + 1;
-  const int64_t span = (int64_t)(PT_BN - 1) * S + 1 + (int64_t)(a.d.KH - 1) * a.d.W + (a.d.KW - 1) + rows_crossed * row_extra +
-                       imgs_crossed * (img_extra > 0 ? img_extra : 0);
-  // 32-bit pixel arithmetic and exact one-multiply division in the kernel
   const int64_t hw = (int64_t)a.OH * a.OW, in_px = (int64_t)a.d.B * a.d.H * a.d.W;
-  if ((a.N + PT_BN) * hw >= ((int64_t)1 << 32) || in_px * (a.d.C / 2) >= ((int64_t)1 << 40)) return false;
-  if (in_px + span >= ((int64_t)1 << 31) / (a.d.C + 16)) return false;
   const int rs = a.d.C + 16;
+  // widest run of flattened input pixels a tile of bn output pixels touches
+  auto span_of = [&](int64_t bn) -> int64_t {
+    const int64_t rows_crossed = (bn + a.OW - 1) / a.OW + 1, imgs_crossed = (bn + hw - 1) / hw + 1;
+    return (bn - 1) * S + 1 + (int64_t)(a.d.KH - 1) * a.d.W + (a.d.KW - 1) + rows_crossed * row_extra +
+           imgs_crossed * (img_extra > 0 ? img_extra : 0);
+  };
+  const int n_pairs = (a.w.n_tiles + 1) / 2;
+  // Four waves per output block when the grid would otherwise leave more than half of the
+  // compute units idle (and a tap holds a multiple of four K steps): twice the work-groups, each
+  // with half the K loop.  With both splits able to fill the chip the two-way split is faster
+  // (measured): less partial-sum traffic, and two work-groups on a compute unit mostly compete
+  // for the same vector-instruction issue slots.
+  int ks = 2;
+  if (cpt % 4 == 0 && (a.N + pt_bn(2) - 1) / pt_bn(2) * n_pairs <= 128) ks = 4;
+  const int64_t bn = pt_bn(ks);
+  const int64_t span = span_of(bn);
+  // 32-bit pixel arithmetic and exact one-multiply division in the kernel
+  if ((a.N + bn) * hw >= ((int64_t)1 << 32) || in_px * (a.d.C / 2) >= ((int64_t)1 << 40)) return false;
+  if (in_px + span >= ((int64_t)1 << 31) / rs) return false;
   const size_t need = (size_t)(span + 1) * rs;  // patch + zero-point row
   // One tile pair per work-group (the exchange buffer overlays the patch) unless the patch is so
   // large that only one work-group fits a compute unit anyway: then a work-group keeps its patch
   // and runs through several pairs, as long as the grid still fills the chip.
-  const size_t lds_single = PHASE_LDS_BYTES + PT_META_BYTES + (need > PT_XCH_BYTES ? need : (size_t)PT_XCH_BYTES);
-  const size_t lds_multi = PHASE_LDS_BYTES + PT_META_BYTES + PT_XCH_BYTES + need;
+  const size_t xch = (size_t)pt_xch_bytes(ks);
+  const size_t lds_single = PHASE_LDS_BYTES + PT_META_BYTES + (need > xch ? need : xch);
+  const size_t lds_multi = PHASE_LDS_BYTES + PT_META_BYTES + xch + need;
   if (lds_single > 160 * 1024) return false;
-  const int64_t gx = (a.N + PT_BN - 1) / PT_BN;
-  const int n_pairs = (a.w.n_tiles + 1) / 2;
+  const int64_t gx = (a.N + bn - 1) / bn;
   int64_t ppw = 1;
-  if (lds_single > 80 * 1024 && lds_multi <= 160 * 1024) {
+  if (ks == 2 && lds_single > 80 * 1024 && lds_multi <= 160 * 1024) {
     ppw = gx * n_pairs / 256;
     ppw = ppw < 1 ? 1 : ppw > n_pairs ? n_pairs : ppw;
   }
   const int gy = (int)((n_pairs + ppw - 1) / ppw);
   ppw = (n_pairs + gy - 1) / gy;
-  g->row_stride = rs;
-  g->patch_rows = (int)span;
-  g->magic_hw = div_magic(hw);
-  g->magic_ow = div_magic(a.OW);
-  *lds_bytes = ppw == 1 ? lds_single : lds_multi;
-  *pairs_per_wg = (int)ppw;
   if ((gx + 7) / 8 * 8 * gy > 0x7fffffff) return false;
-  g->gx = (int)gx;
-  g->gy = gy;
-  *grid = dim3((unsigned)((gx + 7) / 8 * 8 * gy), 1, 1);
-  *pa = a;
+  plan->a = a;
+  plan->g.gx = (int)gx;
+  plan->g.gy = gy;
+  plan->g.row_stride = rs;
+  plan->g.patch_rows = (int)span;
+  plan->g.magic_hw = div_magic(hw);
+  plan->g.magic_ow = div_magic(a.OW);
+  plan->lds = ppw == 1 ? lds_single : lds_multi;
+  plan->blocks = (unsigned)((gx + 7) / 8 * 8 * gy);
+  plan->ks = ks;
+  plan->pairs_per_wg = (int)ppw;
   return true;
 }
 
 // Dynamic LDS above 64 KiB must be allowed per kernel once (per device); remember what was set.
 template <int TAPS, int CPT>
-static int launch_patch_t(const GemmArgs& a, PatchGeom g, size_t lds, dim3 grid, int pairs_per_wg, hipStream_t s) {
+static int launch_patch_t(const PatchPlan& p, hipStream_t s) {
   static bool allowed[64] = {false};
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
@@ -1097,20 +1163,32 @@ static int launch_patch_t(const GemmArgs& a, PatchGeom g, size_t lds, dim3 grid,
     e = hipFuncSetAttribute((const void*)conv_patch_multi_kernel<TAPS, CPT>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return (int)e;
+    if constexpr (CPT % 4 == 0) {
+      e = hipFuncSetAttribute((const void*)conv_patch_split4_kernel<TAPS, CPT>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (e != hipSuccess) return (int)e;
+    }
     allowed[dev] = true;
   }
-  if (pairs_per_wg == 1)
-    hipLaunchKernelGGL((conv_patch_kernel<TAPS, CPT>), grid, dim3(PT_THREADS), lds, s, a, g);
-  else
-    hipLaunchKernelGGL((conv_patch_multi_kernel<TAPS, CPT>), grid, dim3(PT_THREADS), lds, s, a, g, pairs_per_wg);
+  const dim3 grid(p.blocks), block(PT_THREADS);
+  if (p.pairs_per_wg > 1) {
+    hipLaunchKernelGGL((conv_patch_multi_kernel<TAPS, CPT>), grid, block, p.lds, s, p.a, p.g, p.pairs_per_wg);
+  } else if (p.ks == 4) {
+    if constexpr (CPT % 4 == 0)
+      hipLaunchKernelGGL((conv_patch_split4_kernel<TAPS, CPT>), grid, block, p.lds, s, p.a, p.g);
+    else
+      return (int)hipErrorInvalidValue;
+  } else {
+    hipLaunchKernelGGL((conv_patch_kernel<TAPS, CPT>), grid, block, p.lds, s, p.a, p.g);
+  }
   return (int)hipGetLastError();
 }
 
-static int launch_patch(const GemmArgs& a, PatchGeom g, size_t lds, dim3 grid, int pairs_per_wg, hipStream_t s) {
-  const int taps = a.d.KH * a.d.KW;
-  const int cpt = a.d.C / KSTEP;
+static int launch_patch(const PatchPlan& p, hipStream_t s) {
+  const int taps = p.a.d.KH * p.a.d.KW;
+  const int cpt = p.a.d.C / KSTEP;
 #define RMSMP_PATCH_CASE(TP, CP) \
-  if (taps == TP && cpt == CP) return launch_patch_t<TP, CP>(a, g, lds, grid, pairs_per_wg, s);
+  if (taps == TP && cpt == CP) return launch_patch_t<TP, CP>(p, s);
   RMSMP_PATCH_CASE(9, 2)
   RMSMP_PATCH_CASE(9, 4)
   RMSMP_PATCH_CASE(9, 8)
@@ -1417,12 +1495,8 @@ int launch_gemm(const GemmArgs& a, void* stream) {
   if (conv_rows_applies(a)) return launch_conv_rows(a, s);
   if (!a.conv && skinny_applies(a)) return a.N <= 32 ? launch_skinny_t<1>(a, s) : launch_skinny_t<2>(a, s);
   {
-    GemmArgs pa;
-    PatchGeom g;
-    size_t lds;
-    dim3 grid;
-    int ppw;
-    if (patch_kernel_applies(a, &pa, &g, &lds, &grid, &ppw)) return launch_patch(pa, g, lds, grid, ppw, s);
+    PatchPlan plan;
+    if (patch_kernel_applies(a, &plan)) return launch_patch(plan, s);
   }
   if (a.conv) return a.ep.act_bits == 4 ? launch_general<4, true, true>(a, s) : launch_general<8, true, true>(a, s);
   const bool vec = (a.K % 16) == 0;
