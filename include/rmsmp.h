@@ -182,6 +182,33 @@ rmsmp_status rmsmp_conv2d(const rmsmp_packed* Wp, const void* X, const rmsmp_con
 rmsmp_status rmsmp_conv2d_workspace_size(const rmsmp_packed* Wp, const rmsmp_conv_desc* d,
                                          int32_t act_bits, size_t* bytes);
 
+/*
+ * Weight side of one quantization-aware training step (Alg. 1, loop body), on the device.
+ *
+ * rmsmp_fake_quant_rows -- forward: What = proj_S(W).  Row r is projected on the level set of
+ *   scheme[r] with its own scaling factor, exactly as rmsmp_pack_weights does (Eq. 1-4), and
+ *   written back in fp32 as rowscale_r * integer level: the value the packed inference path
+ *   multiplies with, bit for bit.
+ *     W, What    DEVICE fp32 [M][K] row-major (may not overlap)
+ *     scheme     DEVICE, M bytes, each an rmsmp_scheme (device data, not checked: a code above
+ *                2 is treated as RMSMP_FIXED8)
+ *     alpha      DEVICE fp32 [M] or NULL.  NULL: alpha_r = max_k |W[r][k]| (all-zero row: 1)
+ *     alpha_out  DEVICE fp32 [M] or NULL: receives the alpha used
+ * rmsmp_ste_backward -- backward, the straight-through estimator (Eq. 5): the gradient with
+ *   respect to the projected weights is handed to the weights unchanged (rounding has
+ *   derivative 1); the clip in front of the rounding has derivative 0 outside
+ *   [-alpha, alpha], so dW[r][k] = 0 where |W[r][k]| > alpha[r].
+ *     alpha      DEVICE fp32 [M] or NULL.  NULL (alpha was the row maximum): nothing was
+ *                clipped, dW = dWhat and W is not read (may be NULL)
+ *     W, dWhat, dW  DEVICE fp32 [M][K]
+ * Both are asynchronous on `stream`, allocate nothing, and own nothing.
+ * Errors: EINVAL (NULL), ESHAPE (negative sizes, M >= 2^31), EHIP.
+ */
+rmsmp_status rmsmp_fake_quant_rows(const float* W, int64_t M, int64_t K, const uint8_t* scheme,
+                                   const float* alpha, float* What, float* alpha_out, void* stream);
+rmsmp_status rmsmp_ste_backward(const float* W, const float* alpha, const float* dWhat, int64_t M,
+                                int64_t K, float* dW, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -250,3 +250,31 @@ def assign_by_variance(W, scheme, n_pot4):
     if rc != 0:
         raise MemoryError("oracle_assign_by_variance")
     return s
+
+
+def project_rows_f32(W, scheme, alpha=None):
+    """Alg. 1 forward, weight side: proj_S(W) in fp32 (rowscale * integer level).  Returns (what, alpha)."""
+    W = _f32(W)
+    M, K = W.shape
+    scheme = _u8(scheme)
+    a_in = None if alpha is None else _f32(alpha)
+    what = np.empty((M, K), np.float32)
+    a_out = np.empty(M, np.float32)
+    rc = _L().oracle_project_rows_f32(_p(W, ctypes.c_float), ctypes.c_int64(M), ctypes.c_int64(K),
+                                      _p(scheme, ctypes.c_uint8), _p(a_in, ctypes.c_float),
+                                      _p(what, ctypes.c_float), _p(a_out, ctypes.c_float))
+    if rc != 0:
+        raise ValueError("oracle_project_rows_f32: bad scheme code or alpha (rc=%d)" % rc)
+    return what, a_out
+
+
+def ste_backward(W, dwhat, alpha=None):
+    """Eq. 5: gradient of the projected weights handed to the weights, zero where the clip was active."""
+    W, dwhat = _f32(W), _f32(dwhat)
+    M, K = W.shape
+    assert dwhat.shape == (M, K)
+    a_in = None if alpha is None else _f32(alpha)
+    dw = np.empty((M, K), np.float32)
+    _L().oracle_ste_backward(_p(W, ctypes.c_float), ctypes.c_int64(M), ctypes.c_int64(K), _p(a_in, ctypes.c_float),
+                             _p(dwhat, ctypes.c_float), _p(dw, ctypes.c_float))
+    return dw

@@ -440,3 +440,51 @@ int oracle_assign_by_variance(const float* W, int64_t M, int64_t K, int64_t n_po
   free(idx);
   return 0;
 }
+
+/* ------------------------------------------------------------------ */
+/* Quantization-aware training step (Alg. 1, loop body; Eq. 5, the STE) */
+/* ------------------------------------------------------------------ */
+
+/* Forward: proj_S(W) as fp32 -- every row projected onto the level set of its
+ * own scheme with its own alpha (Eq. 1, Eq. 3), the level written as
+ * rowscale * integer, one fp32 multiply, which is the value the inference path
+ * works with.  alpha_in NULL -> alpha_r = max|w_r| (all-zero row: 1).
+ * alpha_out (nullable) receives the alpha used.  Returns 0 / -1 as
+ * oracle_quantize_rows does. */
+int oracle_project_rows_f32(const float* W, int64_t M, int64_t K, const uint8_t* scheme,
+                            const float* alpha_in, float* what, float* alpha_out) {
+  for (int64_t r = 0; r < M; ++r) {
+    const float* w = W + r * K;
+    float alpha = alpha_in ? alpha_in[r] : oracle_row_alpha(w, K);
+    if (!alpha_in && alpha == 0.0f) alpha = 1.0f;
+    if (!(alpha > 0.0f)) return -1;
+    if (alpha_out) alpha_out[r] = alpha;
+    if (scheme[r] == SCHEME_POT4) {
+      float rowscale = alpha * 0.015625f;
+      for (int64_t k = 0; k < K; ++k) what[r * K + k] = rowscale * (float)oracle_pot4_int(w[k], alpha);
+    } else if (scheme[r] == SCHEME_FIXED4 || scheme[r] == SCHEME_FIXED8) {
+      int m = scheme[r] == SCHEME_FIXED4 ? 4 : 8;
+      float rowscale = alpha / (float)fixed_steps(m);
+      for (int64_t k = 0; k < K; ++k) what[r * K + k] = rowscale * (float)oracle_fixed_code(w[k], alpha, m);
+    } else {
+      return -1;
+    }
+  }
+  return 0;
+}
+
+/* Backward (Eq. 5 and the back-propagation line of Alg. 1): the gradient with
+ * respect to the projected weights is handed to the weights unchanged -- the
+ * derivative of round() is taken as 1.  The clip in front of the rounding
+ * (Section 3.1.1) is an ordinary function whose derivative is 0 outside
+ * [-alpha, alpha], so a weight that was clipped receives no gradient; with
+ * alpha = max|w_r| (alpha_in NULL) nothing is clipped and dW = dWhat. */
+void oracle_ste_backward(const float* W, int64_t M, int64_t K, const float* alpha_in, const float* dwhat,
+                         float* dw) {
+  for (int64_t r = 0; r < M; ++r)
+    for (int64_t k = 0; k < K; ++k) {
+      float g = dwhat[r * K + k];
+      if (alpha_in && fabsf(W[r * K + k]) > alpha_in[r]) g = 0.0f;
+      dw[r * K + k] = g;
+    }
+}

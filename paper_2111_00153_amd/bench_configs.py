@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Times the library on every benchmark configuration (synthetic inputs, one GPU) and prints a table.
 
-    python -m paper_2111_00153_amd.bench_configs [gemm] [conv] [skinny]
+    python -m paper_2111_00153_amd.bench_configs [gemm] [conv] [skinny] [sweep] [extra] [qat]
 
 Protocol: 20 warm-up launches, then five blocks of back-to-back launches on one stream between two
 events; the median block is reported.  Throughput counts 2*M*K*N operations of the logical GEMM
@@ -70,7 +70,7 @@ def gemm_case(cfg, M, K, N, ratio, out_kind, z=0, copies=1, label=""):
     return us
 
 
-def conv_case(cfg, idx, B, geom=None, M=None, ratio=(35, 60, 5)):
+def conv_case(cfg, idx, B, geom=None, M=None, ratio=(35, 60, 5), quiet=False):
     if geom is None:
         name, C, M, k, s, pad, H = si.RESNET18_CONVS[idx]
     else:
@@ -96,9 +96,56 @@ def conv_case(cfg, idx, B, geom=None, M=None, ratio=(35, 60, 5)):
     f = rm.conv2d_launcher(p, X, d, rm.make_epilogue(0.05, 0, bits, None, True, rm.OUT_U4, 2.0), Y, ws)
     us = time_launches([f], iters=100, warm=10)
     ops = 2.0 * M * K * N
-    print("cfg%d %-22s M%-4d K%-5d N%-7d: %9.2f us  %8.1f TOPS" % (cfg, name, M, K, N, us, ops / us / 1e6), flush=True)
+    if not quiet:
+        print("cfg%d %-22s M%-4d K%-5d N%-7d: %9.2f us  %8.1f TOPS" % (cfg, name, M, K, N, us, ops / us / 1e6), flush=True)
     p.free()
     return us, ops
+
+
+# Section 4 / Table 6 ratios, written PoT-4 : Fixed-4 : Fixed-8 as the paper does.
+TABLE6_RATIOS = [(0, 100, 0), (100, 0, 0), (50, 50, 0), (60, 40, 0), (67, 33, 0), (60, 35, 5), (65, 30, 5), (35, 60, 5)]
+
+
+def ratio_sweep():
+    """Throughput against the scheme ratio (Table 6's rows) on configs[1] and on the ResNet-18 stack.
+    On matrix cores every scheme multiplies at the same rate; what changes is the decode work."""
+    for ratio in TABLE6_RATIOS:
+        us1, ops1 = conv_case(1, 0, 32, geom=("configs[1] %d:%d:%d" % ratio, 256, 3, 1, 1, 14), M=256, ratio=ratio)
+        tot_us = tot_ops = 0.0
+        for i in range(len(si.RESNET18_CONVS)):
+            us, ops = conv_case(3, i, 64, ratio=ratio, quiet=True)
+            tot_us += us
+            tot_ops += ops
+        print("sweep PoT4:Fixed4:Fixed8 = %3d:%3d:%2d   configs[1] %6.2f us %7.1f TOPS   ResNet-18 stack %.3f ms %6.1f TOPS"
+              % (ratio + (us1, ops1 / us1 / 1e6, tot_us / 1e3, tot_ops / tot_us / 1e6)), flush=True)
+
+
+def extra_layers():
+    """The inference GEMMs of the paper's models that the five configurations do not cover."""
+    gemm_case(5, 1000, 512, 64, (0, 0, 100), rm.OUT_FP32, label="ResNet-18 FC, Fixed-8 rows")
+    gemm_case(5, 768, 768, 4096, (35, 60, 5), rm.OUT_U4, z=7, label="BERT-base QKV / attention-out shape")
+    gemm_case(5, 768, 3072, 4096, (35, 60, 5), rm.OUT_U4, z=7, label="BERT-base FFN down-projection shape")
+    gemm_case(5, 3072, 768, 512, (35, 60, 5), rm.OUT_U4, z=7, label="BERT-base FFN up-projection, 512 tokens")
+
+
+def qat_kernels():
+    """Weight projection (forward) and straight-through backward on a 16384 x 4096 fp32 tensor (256 MiB in,
+    256 MiB out: larger than the last-level cache, so the rates are HBM rates).  Streaming kernels."""
+    M, K = 16384, 4096
+    rng = si.rng_for(6)
+    W = torch.from_numpy(si.weights_rowscaled(rng, M, K)).to(DEV)
+    G = torch.from_numpy(rng.standard_normal((M, K)).astype(np.float32)).to(DEV)
+    scheme = torch.from_numpy(si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, 35, 60, 5))).to(DEV)
+    out = torch.empty_like(W)
+    alpha = W.abs().amax(dim=1).mul_(0.5).contiguous()
+    cases = [("fake_quant_rows, alpha = row maximum", lambda: rm.rmsmp_fake_quant_rows(W, scheme, out), 8),
+             ("fake_quant_rows, alpha supplied", lambda: rm.rmsmp_fake_quant_rows(W, scheme, out, alpha), 8),
+             ("ste_backward, no clip (copy)", lambda: rm.rmsmp_ste_backward(G, out), 8),
+             ("ste_backward, clip mask", lambda: rm.rmsmp_ste_backward(G, out, W, alpha), 12)]
+    for name, fn, bpe in cases:
+        us = time_launches([fn], iters=20, warm=3)
+        print("qat %-40s M%d K%d: %8.2f us  %7.1f GB/s (%d algorithmic bytes per weight)"
+              % (name, M, K, us, M * K * bpe / us / 1e3, bpe), flush=True)
 
 
 def main():
@@ -122,6 +169,12 @@ def main():
             gemm_case(4, 4096, 4096, N, (40, 50, 10), rm.OUT_FP32, label="warm")
         for N in (1, 8, 64):
             gemm_case(4, 4096, 4096, N, (40, 50, 10), rm.OUT_FP32, copies=58, label="cold")
+    if "sweep" in which:
+        ratio_sweep()
+    if "extra" in which:
+        extra_layers()
+    if "qat" in which:
+        qat_kernels()
 
 
 if __name__ == "__main__":

@@ -52,7 +52,8 @@ _lib = _load()
 
 EXPORTS = ["rmsmp_last_error", "rmsmp_version", "rmsmp_ratio_counts", "rmsmp_assign_by_variance",
            "rmsmp_pack_weights", "rmsmp_free_packed", "rmsmp_packed_info", "rmsmp_unpack_codes",
-           "rmsmp_pack_roundtrip_host", "rmsmp_gemm", "rmsmp_conv2d", "rmsmp_conv2d_workspace_size"]
+           "rmsmp_pack_roundtrip_host", "rmsmp_gemm", "rmsmp_conv2d", "rmsmp_conv2d_workspace_size",
+           "rmsmp_fake_quant_rows", "rmsmp_ste_backward"]
 
 
 def _check(rc):
@@ -216,6 +217,20 @@ def gemm_launcher(p, X, N, ep, Y, stream=None):
             _check(rc)
     launch.keepalive = (p, X, ep, Y)
     return launch
+
+
+def rmsmp_fake_quant_rows(W, scheme, What, alpha=None, alpha_out=None, stream=None):
+    """Device tensors: W, What fp32 [M][K]; scheme uint8 [M]; alpha / alpha_out fp32 [M] or None."""
+    M, K = W.shape
+    _check(_lib.rmsmp_fake_quant_rows(_dev(W), ctypes.c_int64(M), ctypes.c_int64(K), _dev(scheme), _dev(alpha),
+                                      _dev(What), _dev(alpha_out), _stream(stream)))
+
+
+def rmsmp_ste_backward(dWhat, dW, W=None, alpha=None, stream=None):
+    """Device tensors fp32 [M][K]; W and alpha [M] only when the forward pass was given an alpha."""
+    M, K = dWhat.shape
+    _check(_lib.rmsmp_ste_backward(_dev(W), _dev(alpha), _dev(dWhat), ctypes.c_int64(M), ctypes.c_int64(K),
+                                   _dev(dW), _stream(stream)))
 
 
 # ---- storage helpers for callers (nibble packing of activation codes; no arithmetic of the method)

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "librmsmp.so")
-SOURCES = ["csrc/pack_host.cpp", "csrc/kernels.hip", "csrc/api.hip"]
+SOURCES = ["csrc/pack_host.cpp", "csrc/kernels.hip", "csrc/fakequant.hip", "csrc/api.hip"]
 HEADERS = ["csrc/rmsmp_internal.h", "../include/rmsmp.h"]
 
 

@@ -311,4 +311,42 @@ rmsmp_status rmsmp_conv2d(const rmsmp_packed* Wp, const void* X, const rmsmp_con
   return RMSMP_OK;
 }
 
+rmsmp_status rmsmp_fake_quant_rows(const float* W, int64_t M, int64_t K, const uint8_t* scheme, const float* alpha,
+                                   float* What, float* alpha_out, void* stream) {
+  if (M < 0 || K < 0) return fail(RMSMP_ESHAPE, "fake_quant_rows: M, K < 0");
+  if (M == 0 || K == 0) return RMSMP_OK;
+  if (!W || !scheme || !What) return fail(RMSMP_EINVAL, "fake_quant_rows: NULL W, scheme or What");
+  if (M > 0x7fffffff) return fail(RMSMP_ESHAPE, "fake_quant_rows: more than 2^31-1 rows");
+  rmsmp::FakeQuantArgs a;
+  a.W = W;
+  a.scheme = scheme;
+  a.alpha = alpha;
+  a.What = What;
+  a.alpha_out = alpha_out;
+  a.M = M;
+  a.K = K;
+  hipError_t e = (hipError_t)rmsmp::launch_fake_quant_rows(a, stream);
+  if (e != hipSuccess) return hip_fail(e, "fake_quant_rows: kernel launch");
+  return RMSMP_OK;
+}
+
+rmsmp_status rmsmp_ste_backward(const float* W, const float* alpha, const float* dWhat, int64_t M, int64_t K,
+                                float* dW, void* stream) {
+  if (M < 0 || K < 0) return fail(RMSMP_ESHAPE, "ste_backward: M, K < 0");
+  if (M == 0 || K == 0) return RMSMP_OK;
+  if (!dWhat || !dW) return fail(RMSMP_EINVAL, "ste_backward: NULL dWhat or dW");
+  if (alpha && !W) return fail(RMSMP_EINVAL, "ste_backward: W is needed when alpha is given");
+  if (M > 0x7fffffff) return fail(RMSMP_ESHAPE, "ste_backward: more than 2^31-1 rows");
+  rmsmp::SteArgs a;
+  a.W = W;
+  a.alpha = alpha;
+  a.dWhat = dWhat;
+  a.dW = dW;
+  a.M = M;
+  a.K = K;
+  hipError_t e = (hipError_t)rmsmp::launch_ste_backward(a, stream);
+  if (e != hipSuccess) return hip_fail(e, "ste_backward: kernel launch");
+  return RMSMP_OK;
+}
+
 }  // extern "C"

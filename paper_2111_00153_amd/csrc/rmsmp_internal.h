@@ -130,6 +130,25 @@ struct Im2colArgs {
   int32_t k_layout = 0;  // KLayout of the columns to produce
 };
 
+// Quantization-aware-training helpers (fakequant.hip); every pointer is a device pointer.
+struct FakeQuantArgs {
+  const float* W = nullptr;       // [M][K]
+  const uint8_t* scheme = nullptr;  // [M]
+  const float* alpha = nullptr;   // [M] or null: per-row maximum
+  float* What = nullptr;          // [M][K]
+  float* alpha_out = nullptr;     // [M] or null
+  int64_t M = 0, K = 0;
+};
+struct SteArgs {
+  const float* W = nullptr;      // [M][K], read only when alpha is given
+  const float* alpha = nullptr;  // [M] or null
+  const float* dWhat = nullptr;  // [M][K]
+  float* dW = nullptr;           // [M][K]
+  int64_t M = 0, K = 0;
+};
+int launch_fake_quant_rows(const FakeQuantArgs& a, void* stream);
+int launch_ste_backward(const SteArgs& a, void* stream);
+
 // Kernel launchers (kernels.hip).  Return hipError_t as int.
 int launch_gemm(const GemmArgs& a, void* stream);
 int launch_im2col(const Im2colArgs& a, void* stream);

@@ -159,3 +159,44 @@ def test_config3_resnet18_layer_small_batch_sampled_dense(rm, oracle, idx):
     """The layers that do not take the stride-1 kernel (conv1, stride-2 3x3, 1x1 downsample), batch 2,
     densely sampled."""
     _resnet_layer(rm, oracle, idx, 2, 20000)
+
+
+# ---- the inference GEMMs of the paper's models that the five configurations do not cover
+
+@pytest.mark.parametrize("name,M,K,N,ratio,bits", [
+    ("resnet18_fc_fixed8_rows", 1000, 512, 64, (0, 0, 100), 4),
+    ("resnet18_fc_w8a8", 1000, 512, 64, (0, 0, 100), 8),
+    ("bert_qkv_shape", 768, 768, 4096, (35, 60, 5), 4),
+    ("bert_ffn_down_shape", 768, 3072, 1024, (35, 60, 5), 4),
+])
+def test_remaining_inference_gemms(rm, oracle, name, M, K, N, ratio, bits):
+    """Last layer of ResNet-18 (Fixed-8 rows; with 4-bit and with 8-bit activations: Section 4 sets
+    first and last layers to 8 bits) and the BERT-base projection shapes; every output compared."""
+    rng = si.rng_for(5, len(name))
+    W = si.weights_bert(rng, M, K) if name.startswith("bert") else si.weights_rowscaled(rng, M, K)
+    scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, *ratio))
+    if bits == 4:
+        xq, s_x, z = si.affine_u4_from_float(rng.standard_normal((N, K)))
+        X = _dev(rm.pack_u4(xq))
+    else:
+        xq, s_x = si.symmetric_i8_from_float(rng.standard_normal((N, K)))
+        z = 0
+        X = _dev(xq)
+    p = rm.rmsmp_pack_weights(W, scheme)
+    ref = oracle.quantize_rows(W, scheme, want_levels=False)
+    acc = oracle.gemm_acc(ref["wint"], xq.astype(np.int32))
+    rs = oracle.rowsum(ref["wint"])
+    acc_c, y, _ = oracle.epilogue(acc, rs, z, ref["rowscale"], s_x, None, True)
+    inv = np.float32(15.0 / float(np.percentile(y, 99.9)))
+    _, _, q = oracle.epilogue(acc, rs, z, ref["rowscale"], s_x, None, True, inv)
+    Yi = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    rm.rmsmp_gemm(p, X, N, rm.make_epilogue(s_x, z, bits, None, False, rm.OUT_INT32), Yi)
+    Yf = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    rm.rmsmp_gemm(p, X, N, rm.make_epilogue(s_x, z, bits, None, True, rm.OUT_FP32), Yf)
+    Yq = torch.empty((N, M // 2), dtype=torch.uint8, device=DEV)
+    rm.rmsmp_gemm(p, X, N, rm.make_epilogue(s_x, z, bits, None, True, rm.OUT_U4, inv), Yq)
+    torch.cuda.synchronize()
+    assert np.array_equal(Yi.cpu().numpy(), acc_c)
+    assert np.all(np.abs(Yf.cpu().numpy() - y) <= 1e-5 * np.abs(y))
+    assert np.array_equal(_grouped_to_rows(rm, Yq.cpu().numpy(), p.perm), q)
+    p.free()
