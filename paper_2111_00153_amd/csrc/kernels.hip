@@ -647,6 +647,94 @@ struct NextPair {
   TileRef tr0, tr1;
 };
 
+// What follows a tile pair's K loop: add the partial sums of the waves that share an output block,
+// then the epilogue.  acc: [weight tile][pixel block] of this wave's 64x64 block.
+template <int KS, bool MULTI, int KIND0, int KIND1>
+__device__ __forceinline__ void pair_tail(const EpArgs& ea, const PatchState& ps, v16i (&acc)[2][2], const TileRef& tr0,
+                                          const TileRef& tr1, bool two) {
+  constexpr int NWT = 4 / KS;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wt = wave % NWT;
+  const int kq = wave / NWT;
+  // ---- add the KS partial sums of a block.  The block's four quarters (weight tile t, pixel
+  // block j: quarter 2t + j) are shared out among the KS waves: wave kq finishes quarters
+  // kq*OWN .. kq*OWN+OWN-1 and parks the others in LDS for their owners.  The roles are KS copies
+  // of the code under a wave-uniform branch, so that which accumulators are given and which are
+  // kept is static (selecting them per element would cost 64 instructions).
+  constexpr int OWN = 4 / KS;  // quarters a wave finishes: 2 (one tile, both pixel blocks) or 1
+  if (!MULTI) __syncthreads();  // the exchange buffer overlays the patch: every wave is done reading it
+  v16i mine[OWN];
+  auto exchange = [&](auto kq_tag) {
+    constexpr int KQ = decltype(kq_tag)::value;
+    // slot [wave of the block][given quarter, in increasing order], 16 registers x 64 lanes each
+    int* const blk = (int*)ps.xch + wt * (KS * (4 - OWN) * 16 * LANES);
+    {
+      int* dst = blk + KQ * ((4 - OWN) * 16 * LANES);
+      int gi = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (q / OWN == KQ) continue;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          v4i gq;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) gq[e] = acc[q >> 1][q & 1][4 * c + e];
+          *(v4i*)(dst + gi * (16 * LANES) + c * (4 * LANES) + lane * 4) = gq;
+        }
+        ++gi;
+      }
+    }
+    __syncthreads();
+    RMSMP_PHASE(4);
+#pragma unroll
+    for (int o = 0; o < OWN; ++o) {
+      constexpr int q0 = KQ * OWN;
+      const int q = q0 + o;
+      mine[o] = acc[q >> 1][q & 1];
+#pragma unroll
+      for (int gk = 0; gk < KS; ++gk) {
+        if (gk == KQ) continue;
+        // where giver gk put quarter q: its given quarters are all but its own, in order
+        const int gi = q < gk * OWN ? q : q - OWN;
+        const int* src = blk + gk * ((4 - OWN) * 16 * LANES) + gi * (16 * LANES);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const v4i got = *(const v4i*)(src + c * (4 * LANES) + lane * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) mine[o][4 * c + e] += got[e];
+        }
+      }
+    }
+  };
+  if (kq == 0)
+    exchange(std::integral_constant<int, 0>{});
+  else if (kq == 1)
+    exchange(std::integral_constant<int, 1>{});
+  else if (KS == 4 && kq == 2)
+    exchange(std::integral_constant<int, KS == 4 ? 2 : 0>{});
+  else if (KS == 4)
+    exchange(std::integral_constant<int, KS == 4 ? 3 : 0>{});
+  // the quarters this wave finishes belong to one weight tile
+  const int my_tile = kq * OWN / 2;
+  if (!(my_tile == 1 && !two)) {
+    RMSMP_PHASE(5);
+    RowMetaLds rm;
+    rm.base = (const int*)__builtin_assume_aligned((const int*)ps.meta + my_tile * TILE_M + 16 * (lane >> 5), 64);
+    rm.rows = 2 * TILE_M;
+    const int n_rows = lane_rows(my_tile ? tr1.nvalid : tr0.nvalid, lane);
+    const int kind = my_tile ? KIND1 : KIND0;
+    const int64_t col0 = (int64_t)ps.n0 + 64 * wt + (lane & 31);
+    if constexpr (OWN == 2) {
+      const int64_t ncol[2] = {col0, col0 + 32};
+      finish_tiles<2>(ea, kind, mine, rm, n_rows, ncol);
+    } else {
+      const int64_t ncol[1] = {col0 + 32 * (kq & 1)};
+      finish_tiles<1>(ea, kind, mine, rm, n_rows, ncol);
+    }
+  }
+}
+
 // One tile pair: weight rings, K loop, partial-sum exchange, epilogue.  KIND0 / KIND1 are the
 // storage classes of the two weight tiles (template parameters so that the K loop has no
 // branches).
@@ -764,82 +852,7 @@ __device__ __forceinline__ void patch_pair(const GemmArgs& a, const EpArgs& ea, 
   RMSMP_PHASE(3);
   // ---- the rings are drained: start the next pair's reads now, behind the exchange and epilogue
   if (MULTI && next.valid) issue_pair_loads<NSTEP, KS>(a, next.mt0, next.mt1, next.tr0, next.tr1, pl);
-  // ---- add the KS partial sums of a block.  The block's four quarters (weight tile t, pixel
-  // block j: quarter 2t + j) are shared out among the KS waves: wave kq finishes quarters
-  // kq*OWN .. kq*OWN+OWN-1 and parks the others in LDS for their owners.  The roles are KS copies
-  // of the code under a wave-uniform branch, so that which accumulators are given and which are
-  // kept is static (selecting them per element would cost 64 instructions).
-  constexpr int OWN = 4 / KS;  // quarters a wave finishes: 2 (one tile, both pixel blocks) or 1
-  if (!MULTI) __syncthreads();  // the exchange buffer overlays the patch: every wave is done reading it
-  v16i mine[OWN];
-  auto exchange = [&](auto kq_tag) {
-    constexpr int KQ = decltype(kq_tag)::value;
-    // slot [wave of the block][given quarter, in increasing order], 16 registers x 64 lanes each
-    int* const blk = (int*)ps.xch + wt * (KS * (4 - OWN) * 16 * LANES);
-    {
-      int* dst = blk + KQ * ((4 - OWN) * 16 * LANES);
-      int gi = 0;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        if (q / OWN == KQ) continue;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          v4i gq;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) gq[e] = acc[q >> 1][q & 1][4 * c + e];
-          *(v4i*)(dst + gi * (16 * LANES) + c * (4 * LANES) + lane * 4) = gq;
-        }
-        ++gi;
-      }
-    }
-    __syncthreads();
-    RMSMP_PHASE(4);
-#pragma unroll
-    for (int o = 0; o < OWN; ++o) {
-      constexpr int q0 = KQ * OWN;
-      const int q = q0 + o;
-      mine[o] = acc[q >> 1][q & 1];
-#pragma unroll
-      for (int gk = 0; gk < KS; ++gk) {
-        if (gk == KQ) continue;
-        // where giver gk put quarter q: its given quarters are all but its own, in order
-        const int gi = q < gk * OWN ? q : q - OWN;
-        const int* src = blk + gk * ((4 - OWN) * 16 * LANES) + gi * (16 * LANES);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const v4i got = *(const v4i*)(src + c * (4 * LANES) + lane * 4);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) mine[o][4 * c + e] += got[e];
-        }
-      }
-    }
-  };
-  if (kq == 0)
-    exchange(std::integral_constant<int, 0>{});
-  else if (kq == 1)
-    exchange(std::integral_constant<int, 1>{});
-  else if (KS == 4 && kq == 2)
-    exchange(std::integral_constant<int, KS == 4 ? 2 : 0>{});
-  else if (KS == 4)
-    exchange(std::integral_constant<int, KS == 4 ? 3 : 0>{});
-  // the quarters this wave finishes belong to one weight tile
-  const int my_tile = kq * OWN / 2;
-  if (!(my_tile == 1 && !two)) {
-    RMSMP_PHASE(5);
-    RowMetaLds rm;
-    rm.base = (const int*)__builtin_assume_aligned((const int*)ps.meta + my_tile * TILE_M + 16 * (lane >> 5), 64);
-    rm.rows = 2 * TILE_M;
-    const int n_rows = lane_rows(my_tile ? tr1.nvalid : tr0.nvalid, lane);
-    const int kind = my_tile ? KIND1 : KIND0;
-    const int64_t col0 = (int64_t)ps.n0 + 64 * wt + (lane & 31);
-    if constexpr (OWN == 2) {
-      const int64_t ncol[2] = {col0, col0 + 32};
-      finish_tiles<2>(ea, kind, mine, rm, n_rows, ncol);
-    } else {
-      const int64_t ncol[1] = {col0 + 32 * (kq & 1)};
-      finish_tiles<1>(ea, kind, mine, rm, n_rows, ncol);
-    }
-  }
+  pair_tail<KS, MULTI, KIND0, KIND1>(ea, ps, acc, tr0, tr1, two);
   RMSMP_PHASE(6);
 }
 
