@@ -1,35 +1,70 @@
 """Builds librmsmp.so (hipcc, gfx950 only) next to this file."""
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "librmsmp.so")
-SOURCES = ["csrc/pack_host.cpp", "csrc/kernels.hip", "csrc/fakequant.hip", "csrc/api.hip"]
-HEADERS = ["csrc/rmsmp_internal.h", "../include/rmsmp.h"]
+OBJ_DIR = os.path.join(HERE, "_build")
+SOURCES = ["csrc/pack_host.cpp", "csrc/kernels.hip", "csrc/patch_wide.hip", "csrc/fakequant.hip", "csrc/api.hip"]
+HEADERS = ["csrc/rmsmp_internal.h", "csrc/device_common.h", "csrc/patch_wide.h", "../include/rmsmp.h"]
+# (filter taps, channels / 32) families of the wide LDS-resident kernel: csrc/patch_wide_inst.hip is
+# compiled once per family so that they build in parallel
+WIDE_FAMILIES = [(9, 2), (9, 4), (9, 8), (9, 16), (1, 2), (1, 4), (1, 8), (1, 16), (1, 24)]
+WIDE_SOURCE = "csrc/patch_wide_inst.hip"
+
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+         # packed-FP32 VALU forms are kept off (per-lane fp32 epilogue must be bit-reproducible)
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-ffp-contract=off", "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc")]
 
 
-def hipcc_command():
-    return (["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-             # packed-FP32 VALU forms are kept off (per-lane fp32 epilogue must be bit-reproducible)
-             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-             "-ffp-contract=off", "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc")]
-            + [os.path.join(HERE, s) for s in SOURCES] + ["-o", LIB])
+def _units():
+    """(source, extra defines, object path) of every translation unit."""
+    units = [(s, [], os.path.join(OBJ_DIR, os.path.splitext(os.path.basename(s))[0] + ".o")) for s in SOURCES]
+    for taps, cpt in WIDE_FAMILIES:
+        units.append((WIDE_SOURCE, ["-DRMSMP_WIDE_TAPS=%d" % taps, "-DRMSMP_WIDE_CPT=%d" % cpt],
+                      os.path.join(OBJ_DIR, "patch_wide_inst_%d_%d.o" % (taps, cpt))))
+    return units
+
+
+def _compile(unit, extra=()):
+    src, defines, obj = unit
+    cmd = ["hipcc"] + FLAGS + defines + list(extra) + ["-c", os.path.join(HERE, src), "-o", obj]
+    subprocess.check_call(cmd, cwd=HERE)
 
 
 def is_stale():
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(os.path.join(HERE, f)) > t for f in SOURCES + HEADERS)
+    return any(os.path.getmtime(os.path.join(HERE, f)) > t for f in SOURCES + [WIDE_SOURCE] + HEADERS)
 
 
-def build_library(force=True):
-    """Compile the library.  force=False only compiles when the .so is missing."""
-    if force or not os.path.exists(LIB):
-        subprocess.check_call(hipcc_command(), cwd=HERE)
+def build_library(force=True, only_changed=False, extra=()):
+    """Compile the library: one object per source (in parallel), then one link.
+
+    force=False only compiles when the .so is missing; only_changed=True (a development
+    convenience) reuses objects that are newer than their source and every header."""
+    if not force and os.path.exists(LIB):
+        return LIB
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    hdr_time = max(os.path.getmtime(os.path.join(HERE, h)) for h in HEADERS)
+    todo = []
+    for unit in _units():
+        src, _, o = unit
+        fresh = (only_changed and os.path.exists(o)
+                 and os.path.getmtime(o) > max(hdr_time, os.path.getmtime(os.path.join(HERE, src))))
+        if not fresh:
+            todo.append(unit)
+    with ThreadPoolExecutor(max_workers=min(8, max(1, len(todo)))) as ex:
+        list(ex.map(lambda u: _compile(u, extra), todo))
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC"]
+                          + [u[2] for u in _units()] + ["-o", LIB], cwd=HERE)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build_library())
+    import sys
+    print(build_library(only_changed="--changed" in sys.argv))

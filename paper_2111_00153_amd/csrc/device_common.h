@@ -1,0 +1,359 @@
+// Device-side helpers shared by the kernels of librmsmp (gfx950): MFMA operand types, register-level
+// decode of the three storage classes, tile lookup and the fused epilogue (zero point, per-row
+// scale, bias, ReLU, 4-bit requantization).  Included by every .hip file that holds a GEMM kernel.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <type_traits>
+
+#include "rmsmp_internal.h"
+
+namespace rmsmp {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// Optional per-wave phase timestamps for tuning builds (-DRMSMP_PHASE_TIMING); compiled out
+// otherwise.  A stamp is one clock read parked in the first KiB of dynamic LDS (16 slots per
+// wave); the kernel copies the slots to g_phase_buf when it ends, so a stamp costs no memory
+// round trip where it is taken.
+#ifdef RMSMP_PHASE_TIMING
+__device__ unsigned long long* g_phase_buf = nullptr;
+constexpr int PHASE_LDS_BYTES = 1024;
+extern __shared__ __attribute__((aligned(16))) uint8_t phase_smem[];
+#define RMSMP_PHASE(id)                                                                                  \
+  do {                                                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                                   \
+    if ((threadIdx.x & 63) == 0) ((unsigned long long*)phase_smem)[(threadIdx.x >> 6) * 16 + (id)] = clock64(); \
+    __builtin_amdgcn_sched_barrier(0);                                                                   \
+  } while (0)
+#define RMSMP_PHASE_FLUSH()                                                                              \
+  do {                                                                                                   \
+    if (g_phase_buf && (threadIdx.x & 63) == 0)                                                          \
+      for (int i_ = 0; i_ < 16; ++i_)                                                                    \
+        g_phase_buf[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + i_] =                                  \
+            ((unsigned long long*)phase_smem)[(threadIdx.x >> 6) * 16 + i_];                             \
+  } while (0)
+#else
+constexpr int PHASE_LDS_BYTES = 0;
+#define RMSMP_PHASE(id) \
+  do {                  \
+  } while (0)
+#define RMSMP_PHASE_FLUSH() \
+  do {                      \
+  } while (0)
+#endif
+
+// ---------------------------------------------------------------- operand decode
+
+// Eight two's-complement nibbles per word -> int8 = 16*q, in MFMA slot order.
+__device__ __forceinline__ v4i decode_nib_shift(uint2 w) {
+  v4i a;
+  a.x = (int)((w.x << 4) & 0xf0f0f0f0u);
+  a.y = (int)(w.x & 0xf0f0f0f0u);
+  a.z = (int)((w.y << 4) & 0xf0f0f0f0u);
+  a.w = (int)(w.y & 0xf0f0f0f0u);
+  return a;
+}
+
+// Four nibbles (one per byte of sel, 0..15) through the row's 16-entry byte table.
+__device__ __forceinline__ uint32_t lut4(uint32_t sel, uint4 T) {
+  return __builtin_amdgcn_perm(T.y, T.x, sel) ^ __builtin_amdgcn_perm(T.w, T.z, sel ^ 0x08080808u);
+}
+
+__device__ __forceinline__ v4i decode_nib_lut(uint2 w, uint4 T) {
+  v4i a;
+  a.x = (int)lut4(w.x & 0x0f0f0f0fu, T);
+  a.y = (int)lut4((w.x >> 4) & 0x0f0f0f0fu, T);
+  a.z = (int)lut4(w.y & 0x0f0f0f0fu, T);
+  a.w = (int)lut4((w.y >> 4) & 0x0f0f0f0fu, T);
+  return a;
+}
+
+// Sixteen unsigned 4-bit activation codes (8 bytes) -> int8 0..15 in MFMA slot order.
+__device__ __forceinline__ v4i decode_act_u4(uint2 w) {
+  v4i x;
+  x.x = (int)(w.x & 0x0f0f0f0fu);
+  x.y = (int)((w.x >> 4) & 0x0f0f0f0fu);
+  x.z = (int)(w.y & 0x0f0f0f0fu);
+  x.w = (int)((w.y >> 4) & 0x0f0f0f0fu);
+  return x;
+}
+
+// Sixteen int8 activation codes in memory order -> MFMA slot order (even elements, then odd).
+__device__ __forceinline__ v4i reorder_act_i8(uint4 w) {
+  v4i x;
+  x.x = (int)__builtin_amdgcn_perm(w.y, w.x, 0x06040200u);
+  x.y = (int)__builtin_amdgcn_perm(w.y, w.x, 0x07050301u);
+  x.z = (int)__builtin_amdgcn_perm(w.w, w.z, 0x06040200u);
+  x.w = (int)__builtin_amdgcn_perm(w.w, w.z, 0x07050301u);
+  return x;
+}
+
+// Packed weight fragment of one K step as it sits in memory (per lane): 8 bytes of nibbles or
+// 16 bytes of int8.
+template <int KIND>
+struct RawFrag {
+  typedef uint2 type;
+};
+template <>
+struct RawFrag<TILE_I8> {
+  typedef uint4 type;
+};
+
+template <int KIND>
+__device__ __forceinline__ typename RawFrag<KIND>::type load_raw(const uint8_t* lane_ptr, int64_t step_bytes_index) {
+  return *(const typename RawFrag<KIND>::type*)(lane_ptr + step_bytes_index);
+}
+// same, from a wave-uniform base and a 32-bit per-lane byte offset
+template <int KIND>
+__device__ __forceinline__ typename RawFrag<KIND>::type load_raw(const uint8_t* uniform_base, uint32_t lane_off) {
+  return *(const typename RawFrag<KIND>::type*)(uniform_base + lane_off);
+}
+
+template <int KIND>
+__device__ __forceinline__ v4i decode_raw(typename RawFrag<KIND>::type w, uint4 T);
+template <>
+__device__ __forceinline__ v4i decode_raw<TILE_NIB_SHIFT>(uint2 w, uint4) {
+  return decode_nib_shift(w);
+}
+template <>
+__device__ __forceinline__ v4i decode_raw<TILE_NIB_LUT>(uint2 w, uint4 T) {
+  return decode_nib_lut(w, T);
+}
+template <>
+__device__ __forceinline__ v4i decode_raw<TILE_I8>(uint4 w, uint4) {
+  return (v4i){(int)w.x, (int)w.y, (int)w.z, (int)w.w};
+}
+
+// ---------------------------------------------------------------- tile lookup
+
+// Class, live rows and blob offset of weight tile mt, from the class sizes alone (no memory access).
+__device__ __forceinline__ TileRef tile_ref(const DevicePacked& w, int mt) {
+  const int64_t nib_tile = (int64_t)w.nks * LANES * 8, i8_tile = (int64_t)w.nks * LANES * 16;
+  const int t0 = w.class_tiles[0], t1 = w.class_tiles[1];
+  TileRef t;
+  int idx;
+  if (mt < t0) {
+    t.kind = TILE_NIB_SHIFT;
+    idx = mt;
+    t.blob_off = (int64_t)mt * nib_tile;
+  } else if (mt < t0 + t1) {
+    t.kind = TILE_NIB_LUT;
+    idx = mt - t0;
+    t.blob_off = (int64_t)mt * nib_tile;
+  } else {
+    t.kind = TILE_I8;
+    idx = mt - t0 - t1;
+    t.blob_off = (int64_t)(t0 + t1) * nib_tile + (int64_t)idx * i8_tile;
+  }
+  const int left = w.class_rows[t.kind] - idx * TILE_M;
+  t.nvalid = left < TILE_M ? left : TILE_M;
+  return t;
+}
+
+// ---------------------------------------------------------------- epilogue
+
+// Every fp32 operation is rounded on its own so that codes are reproducible bit for bit.
+// What the epilogue needs from the kernel arguments.  Kernel arguments are fetched with scalar
+// loads where they are first used; at the end of a kernel that is a cold miss in front of the
+// stores, so kernels copy these fields at their start and pin them in registers.
+// The epilogue's pointers pass through an empty asm (see pin_epilogue_args), which hides from the
+// compiler that they point to global memory; without the explicit address space it would emit
+// flat loads and stores, whose completion it cannot count and therefore waits for in full.
+#define RMSMP_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ RMSMP_GLOBAL T* as_global(T* p) {
+  return (RMSMP_GLOBAL T*)p;
+}
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+
+struct EpArgs {
+  void* Y;
+  const float* bias;
+  int64_t N, M;
+  float act_scale, out_inv_scale;
+  int zp, relu, out_kind;
+  bool stamps = false;  // tuning builds: this kernel reserved the stamp slots in LDS
+};
+
+__device__ __forceinline__ EpArgs pin_epilogue_args(const GemmArgs& a) {
+  EpArgs e;
+  e.Y = a.Y;
+  e.bias = a.ep.bias;
+  e.N = a.N;
+  e.M = a.M;
+  e.act_scale = a.ep.act_scale;
+  e.out_inv_scale = a.ep.out_inv_scale;
+  e.zp = a.ep.act_zero_point;
+  e.relu = a.ep.relu;
+  e.out_kind = a.ep.out_kind;
+  // an empty asm that "modifies" the values keeps the loads here
+  asm volatile("" : "+s"(e.Y), "+s"(e.bias), "+s"(e.N), "+s"(e.M), "+s"(e.act_scale), "+s"(e.out_inv_scale), "+s"(e.zp),
+               "+s"(e.relu), "+s"(e.out_kind));
+  return e;
+}
+
+// Row metadata of the 16 consecutive grouped rows a lane finishes, held in registers:
+// {rowscale bits, rowsum, original row (-1 = padding), grouped position} per row.
+struct RowMeta {
+  int4 m[16];
+  __device__ __forceinline__ int scale_bits(int r) const { return m[r].x; }
+  __device__ __forceinline__ int rowsum(int r) const { return m[r].y; }
+  __device__ __forceinline__ int orig(int r) const { return m[r].z; }
+  __device__ __forceinline__ int gpos0() const { return m[0].w; }
+};
+
+// The same, read on demand from a table in LDS laid out field by field (rows x 4 fields): an
+// epilogue then only touches the fields its output kind needs and keeps few of them in registers.
+struct RowMetaLds {
+  const int* base;  // LDS: field f of the lane's row r at base[f * rows + r]
+  int rows;
+  __device__ __forceinline__ int scale_bits(int r) const { return base[r]; }
+  __device__ __forceinline__ int rowsum(int r) const { return base[rows + r]; }
+  __device__ __forceinline__ int orig(int r) const { return base[2 * rows + r]; }
+  __device__ __forceinline__ int gpos0() const { return base[3 * rows]; }
+};
+
+__device__ __forceinline__ void load_row_meta(const DevicePacked& w, int mt, int lane, RowMeta& rm) {
+  const int4* src = (const int4*)w.p_meta + (int64_t)mt * TILE_M + 16 * (lane >> 5);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) rm.m[r] = src[r];
+}
+
+// 4-bit output codes of one pixel block: clamp(rint(y * inv_s), 0, 15) for the lane's 16 rows,
+// row r in nibble r of the 64-bit result.  BIAS / RELU say which of the optional steps exist, so
+// that the common cases carry no dead instructions.  The float-to-byte conversion packs a value
+// that is already an exact integer in [0, 15], so its own rounding mode plays no role.
+template <bool BIAS, bool RELU>
+__device__ __forceinline__ void requant_block(const v16i& v, const float (&m)[16], const float (&bias)[16], float inv_s,
+                                              uint32_t (&packed)[2]) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    uint32_t even = 0u, odd = 0u;  // bytes: rows 8h + {0,2,4,6} and 8h + {1,3,5,7}
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = 8 * h + i;
+      float y = __fmul_rn((float)v[r], m[r]);
+      if (BIAS) y = __fadd_rn(y, bias[r]);
+      if (RELU) y = fmaxf(y, 0.0f);
+      const float t = __builtin_amdgcn_fmed3f(rintf(__fmul_rn(y, inv_s)), 0.0f, 15.0f);
+      if (i & 1)
+        odd = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, odd);
+      else
+        even = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, even);
+    }
+    packed[h] = even | (odd << 4);
+  }
+}
+
+// Finish NB 32x32 accumulator tiles of the same weight tile (NB pixel blocks): zero-point
+// correction, per-row scale, bias, ReLU, then int32 / fp32 / nibble-packed 4-bit store.
+// Register r of lane l is grouped row 16*(l/32)+r of the weight tile and column n[j]; the 16
+// registers of a lane are 16 consecutive grouped rows.  n_rows = how many of the lane's 16 rows
+// exist (live rows of a tile are a prefix).  Straight-line code: padding rows are computed and
+// dropped at the store, and all results are formed before the first store is issued (a store
+// pins its data registers until it has left, so interleaving would stall on every block).
+//
+// Accumulators of shift-decoded tiles are 16 times the true sums.  The integer output divides
+// them (an exact shift); the float paths fold the factor into the per-row multiplier instead:
+// float(16 a) * (m / 16) and float(a) * m are the same float, because scaling by a power of two
+// commutes with rounding.
+template <int NB, class Meta>
+__device__ __forceinline__ void finish_tiles(const EpArgs& a, int kind, const v16i (&acc)[NB], const Meta& rm,
+                                             int n_rows, const int64_t (&n)[NB]) {
+  if (n_rows <= 0) return;
+  const int zp = a.zp;
+  const bool has_bias = a.bias != nullptr;
+  const bool relu = a.relu != 0;
+  const int out_kind = a.out_kind;
+  const bool x16 = kind == TILE_NIB_SHIFT;
+  v16i v[NB];
+#pragma unroll
+  for (int j = 0; j < NB; ++j) v[j] = acc[j];
+  if (out_kind == 0) {
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int s = (x16 ? v[j][r] >> 4 : v[j][r]) - zp * rm.rowsum(r);
+        if (r < n_rows && n[j] < a.N) as_global((int32_t*)a.Y)[(int64_t)rm.orig(r) * a.N + n[j]] = s;
+      }
+    return;
+  }
+  if (zp != 0) {
+    const int zs = x16 ? 16 * zp : zp;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int c = zs * rm.rowsum(r);
+#pragma unroll
+      for (int j = 0; j < NB; ++j) v[j][r] -= c;
+    }
+  }
+  if (a.stamps) RMSMP_PHASE(8);
+  float bias[16], m[16];
+  const float fold = x16 ? 0.0625f : 1.0f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    bias[r] = 0.0f;
+    m[r] = __fmul_rn(__fmul_rn(__int_as_float(rm.scale_bits(r)), a.act_scale), fold);
+  }
+  if (has_bias) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) bias[r] = as_global(a.bias)[rm.orig(r) < 0 ? 0 : rm.orig(r)];
+  }
+  if (out_kind == 1) {
+    // adding a zero bias and taking the maximum with -inf change nothing, so one code path serves
+    // every combination of the two options
+    const float floor_y = relu ? 0.0f : -__builtin_inff();
+    float y[NB][16];
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) y[j][r] = fmaxf(__fadd_rn(__fmul_rn((float)v[j][r], m[r]), bias[r]), floor_y);
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (r < n_rows && n[j] < a.N) as_global((float*)a.Y)[(int64_t)rm.orig(r) * a.N + n[j]] = y[j][r];
+    return;
+  }
+  if (a.stamps) RMSMP_PHASE(12);
+  // with a positive output scale the clamp at code 0 already does what ReLU would (a negative y
+  // rounds to a non-positive value), so the separate maximum is skipped
+  const bool relu_q = relu && !(a.out_inv_scale > 0.0f);
+  uint32_t packed[NB][2];
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    if (has_bias) {
+      if (relu_q)
+        requant_block<true, true>(v[j], m, bias, a.out_inv_scale, packed[j]);
+      else
+        requant_block<true, false>(v[j], m, bias, a.out_inv_scale, packed[j]);
+    } else {
+      if (relu_q)
+        requant_block<false, true>(v[j], m, bias, a.out_inv_scale, packed[j]);
+      else
+        requant_block<false, false>(v[j], m, bias, a.out_inv_scale, packed[j]);
+    }
+  }
+  if (a.stamps) RMSMP_PHASE(13);
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    if (n[j] >= a.N) continue;
+    // the first grouped position of a lane is a multiple of 16
+    RMSMP_GLOBAL uint8_t* dst = as_global((uint8_t*)a.Y) + n[j] * (a.M / 2) + (rm.gpos0() >> 1);
+    if (n_rows == 16 && (((uintptr_t)dst) & 7) == 0) {
+      *(RMSMP_GLOBAL v2u*)dst = (v2u){packed[j][0], packed[j][1]};
+    } else {
+      for (int b = 0; b < n_rows / 2; ++b) dst[b] = (uint8_t)(packed[j][b >> 2] >> (8 * (b & 3)));
+    }
+  }
+  if (a.stamps) RMSMP_PHASE(9);
+}
+
+__device__ __forceinline__ int lane_rows(int nvalid, int lane) {
+  const int left = nvalid - 16 * (lane >> 5);
+  return left < 0 ? 0 : left > 16 ? 16 : left;
+}
+
+}  // namespace rmsmp

@@ -1,0 +1,551 @@
+// Wide LDS-resident implicit-im2col kernel of librmsmp (gfx950).
+//
+// Same data flow as the narrower LDS-resident kernel -- the input pixels a work-group needs are
+// read once, decoded to int8 and kept in LDS for all taps; packed weights stream from global
+// memory through a register ring and are decoded in registers -- with two changes that the
+// measurements asked for:
+//
+//  * A wave owns 64 rows x 128 pixels (two weight fragments x four activation fragments, eight
+//    MFMAs per K step).  The decode of a weight fragment is vector-ALU work that shares the issue
+//    port with the MFMAs: at 64 pixels per wave a Fixed-4 + PoT-4 tile pair needs ~8 vector
+//    instructions per MFMA (more than fit under one), at 128 pixels ~4.
+//  * The K loop is a real loop (one filter row, or one tap, per iteration) instead of
+//    straight-line code for all of K.  A kernel starts with a cold instruction cache; code that is
+//    executed once is fetched at memory latency, a loop body is fetched once.
+//
+// The four waves of a work-group are shared out over K quarters (KS), 128-pixel blocks (NWT) and
+// tile pairs (MS), KS*NWT*MS = 4: small grids split K four ways, wide layers put the waves side
+// by side, layers with many rows give every wave its own tile pair against the same patch.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <utility>
+
+#include "device_common.h"
+
+namespace rmsmp {
+
+constexpr int PW_THREADS = 256;
+constexpr int PW_PATCH_UNROLL = 6;  // 16-byte patch pieces in flight per thread
+
+struct WideGeom {
+  int gx, gy;         // pixel tiles, row blocks (the launch grid is one-dimensional)
+  int row_stride;     // LDS bytes per patch pixel (C + 16)
+  int patch_rows;     // pixels staged per work-group
+  uint32_t magic_hw;  // ceil(2^32 / (OH*OW)), 0 when OH*OW == 1
+  uint32_t magic_ow;  // ceil(2^32 / OW), 0 when OW == 1
+};
+
+// bytes of the partial-sum exchange buffer: every wave parks the blocks it does not finish
+constexpr int pw_xch_bytes(int xb, int ks) { return ks == 1 ? 0 : 4 * (2 * xb - 2 * xb / ks) * 16 * LANES * 4; }
+
+__device__ __forceinline__ int wide_fast_div(int n, uint32_t magic) {
+  return magic ? (int)__umulhi((uint32_t)n, magic) : n;
+}
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+// Packed weight fragments are fetched through a buffer resource: the descriptor and the K-step
+// offset live in scalar registers, the per-lane offset never changes, so stepping through K costs
+// no vector instructions, and a read past the end of the tile returns zeros instead of faulting.
+typedef unsigned v2w __attribute__((ext_vector_type(2)));
+typedef unsigned v4w __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t wide_rsrc(const uint8_t* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
+}
+template <int KIND>
+__device__ __forceinline__ typename RawFrag<KIND>::type wide_load(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, int step_off) {
+  if constexpr (KIND == TILE_I8) {
+    const v4w w = __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, step_off, 0);
+    return make_uint4(w.x, w.y, w.z, w.w);
+  } else {
+    const v2w w = __builtin_amdgcn_raw_buffer_load_b64(r, (int)lane_off, step_off, 0);
+    return make_uint2(w.x, w.y);
+  }
+}
+
+// Word CI (0..3) of a decoded weight fragment: the decode of a fragment is spread over the four
+// pixel blocks of a K step, one word behind each pair of MFMAs.
+template <int KIND, int CI>
+__device__ __forceinline__ int decode_word(const typename RawFrag<KIND>::type& w, const uint4& T) {
+  if constexpr (KIND == TILE_I8) {
+    return (int)(CI == 0 ? w.x : CI == 1 ? w.y : CI == 2 ? w.z : w.w);
+  } else {
+    const uint32_t src = CI < 2 ? w.x : w.y;
+    if constexpr (KIND == TILE_NIB_SHIFT) {
+      return (int)((CI & 1) ? (src & 0xf0f0f0f0u) : ((src << 4) & 0xf0f0f0f0u));
+    } else {
+      return (int)lut4(((CI & 1) ? (src >> 4) : src) & 0x0f0f0f0fu, T);
+    }
+  }
+}
+
+// The first batch of patch reads is issued at the very start of the kernel, before the code of
+// the work-group's class combination is even fetched; this is what it leaves behind.
+struct WidePatchLoads {
+  uint4 pw[PW_PATCH_UNROLL];
+  __amdgpu_buffer_rsrc_t xr;  // the activation tensor
+  uint32_t src0;              // byte offset of the patch in it
+  uint32_t x_last;            // last valid 16-byte read
+  int f_lo;                   // first staged pixel
+};
+
+// 16-byte piece idx of the patch; reads past the end of X are clamped (those rows are never used)
+__device__ __forceinline__ uint4 wide_load_piece(const WidePatchLoads& pl, int idx) {
+  uint32_t off = pl.src0 + (uint32_t)idx * 16u;
+  off = off < pl.x_last ? off : pl.x_last;
+  const v4w w = __builtin_amdgcn_raw_buffer_load_b128(pl.xr, (int)off, 0, 0);
+  return make_uint4(w.x, w.y, w.z, w.w);
+}
+
+// Everything one wave does.  KIND0 / KIND1: storage classes of its two weight tiles.
+template <int TAPS, int CPT, int XB, int KS, int NWT, int MS, int KIND0, int KIND1>
+__device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, const WideGeom& g, int bx, int pair,
+                                          bool pair_live, WidePatchLoads& pl) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+  static_assert(KS * NWT * MS == 4, "four waves");
+  static_assert(XB == 2 || XB == 4, "32-pixel blocks per wave");
+  constexpr int PW_XB = XB;
+  constexpr int PW_WAVE_PX = 32 * XB;
+  static_assert(CPT % KS == 0, "a tap must hold a whole number of K steps per wave");
+  constexpr int C = CPT * KSTEP;
+  constexpr int KW = TAPS == 9 ? 3 : 1;
+  constexpr int KH = KW;
+  constexpr int SPT = CPT / KS;       // K steps per tap and wave
+  constexpr int NSTEP = TAPS * SPT;   // K steps per wave
+  // loop body: one filter row while that stays small, else one tap
+  constexpr int BT = (TAPS == 9 && SPT <= 4) ? 3 : 1;
+  constexpr int BODY = BT * SPT;
+  constexpr int NIT = TAPS / BT;
+  // ring depth: a divisor of the body, so that a step's ring slot is the same in every iteration
+#ifndef RMSMP_WIDE_RING
+#define RMSMP_WIDE_RING 4
+#endif
+  constexpr int R = BODY % RMSMP_WIDE_RING == 0 ? RMSMP_WIDE_RING : BODY % 4 == 0 ? 4 : BODY % 3 == 0 ? 3 : BODY % 2 == 0 ? 2 : 1;
+  static_assert(R <= NSTEP, "ring deeper than the K loop");
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wt = wave % NWT;
+  const int kq = wave / (NWT * MS);
+  const int H = a.d.H, W = a.d.W, pad = a.d.pad, S = a.d.stride;
+  const int hw_out = a.OH * a.OW;
+  const int row_stride = g.row_stride, patch_rows = g.patch_rows;
+  const int n0 = bx * (PW_WAVE_PX * NWT);  // first output pixel of the work-group
+  const int nw = n0 + PW_WAVE_PX * wt;     // and of this wave
+
+  // LDS: row metadata [MS pairs][4 fields][64 rows] | zero-point row (C bytes, +16 pad) | decoded
+  // input patch.  The exchange buffer later lies over the zero-point row and the patch.
+  uint8_t* const meta = smem_raw + PHASE_LDS_BYTES;
+  uint8_t* const zrow = meta + MS * (2 * TILE_M * 16);
+  uint8_t* const patch = zrow + (C + 16);
+  uint8_t* const xch = zrow;
+
+  const int mt0 = pair, mt1 = a.w.n_tiles - 1 - pair;
+  const TileRef tr0 = tile_ref(a.w, mt0), tr1 = tile_ref(a.w, mt1);
+  const bool two = mt1 > mt0;
+
+  // flattened input index of tap (0,0) for output pixel n (may be negative / out of image)
+  auto base_index = [&](int n, int& oh, int& ow) -> int {
+    const int b = wide_fast_div(n, g.magic_hw);
+    const int rem = n - b * hw_out;
+    oh = wide_fast_div(rem, g.magic_ow);
+    ow = rem - oh * a.OW;
+    return (b * H + (oh * S - pad)) * W + (ow * S - pad);
+  };
+  const int f_lo = pl.f_lo;
+
+  // ---- weight stream of this wave: uniform base of its first K step + 32-bit lane offset
+  constexpr int fb0 = KIND0 == TILE_I8 ? 16 : 8, fb1 = KIND1 == TILE_I8 ? 16 : 8;
+  constexpr int step0 = LANES * fb0, step1 = LANES * fb1;  // bytes per K step
+  const __amdgpu_buffer_rsrc_t wb0 = wide_rsrc(a.w.blob + tr0.blob_off, (uint32_t)(CPT * TAPS) * step0);
+  const __amdgpu_buffer_rsrc_t wb1 = wide_rsrc(a.w.blob + tr1.blob_off, (uint32_t)(CPT * TAPS) * step1);
+  const uint32_t wl0 = (uint32_t)lane * fb0 + kq * step0, wl1 = (uint32_t)lane * fb1 + kq * step1;
+  typename RawFrag<KIND0>::type ring0[R];
+  typename RawFrag<KIND1>::type ring1[R];
+  uint4 T0 = make_uint4(0, 0, 0, 0), T1 = T0;
+  int4 meta_row = make_int4(0, 0, 0, 0);
+
+  // ---- 1. the first batch of the patch is on its way; now what the wave's tile pair needs.
+  // Pixels f_lo .. f_lo+patch_rows-1 are one contiguous byte range of X; piece idx (32 channels,
+  // 16 bytes) sits at byte 16*idx of it and goes, decoded to int8, to LDS byte
+  // 32*idx + 16*(idx / pieces-per-pixel) (rows are padded by 16 bytes).
+  constexpr int PIECES = C / 32;
+  const int total = patch_rows * PIECES;
+  auto put_piece = [&](int idx, uint4 w) {
+    uint8_t* dst = patch + idx * 32 + (idx / PIECES) * 16;
+    *(v4i*)dst = decode_act_u4(make_uint2(w.x, w.y));
+    *(v4i*)(dst + 16) = decode_act_u4(make_uint2(w.z, w.w));
+  };
+  uint4 (&pw)[PW_PATCH_UNROLL] = pl.pw;
+#pragma unroll
+  for (int u = 0; u < R; ++u) {
+    ring0[u] = wide_load<KIND0>(wb0, wl0, u * KS * step0);
+    ring1[u] = wide_load<KIND1>(wb1, wl1, u * KS * step1);
+  }
+  if (KIND0 == TILE_NIB_LUT) T0 = *(const uint4*)(a.w.p_lut + ((int64_t)mt0 * TILE_M + tile_row_goff(lane & 31)) * 4);
+  if (KIND1 == TILE_NIB_LUT) T1 = *(const uint4*)(a.w.p_lut + ((int64_t)mt1 * TILE_M + tile_row_goff(lane & 31)) * 4);
+  // the wave with kq == 0 (and wt == 0) of a pair fetches its row metadata: lanes 0..31 tile 0, 32..63 tile 1
+  if (kq == 0 && wt == 0) meta_row = ((const int4*)a.w.p_meta)[(lane < TILE_M ? mt0 : mt1) * TILE_M + (lane & (TILE_M - 1))];
+  __builtin_amdgcn_sched_barrier(0);
+  RMSMP_PHASE(11);
+
+  // ---- 2. while those are in flight: accumulators, and per lane and 32-pixel block the LDS
+  // address of tap (0,0), counted from the zero-point row, and the taps inside the image.
+  // Validity is separable: tap (kh,kw) is inside iff kh is in [kh_lo,kh_hi] and kw in
+  // [kw_lo,kw_hi].  A tap outside reads the zero-point row: its address is 0 whatever the lane, so
+  // a tap's address is (address if inside) & (0 or -1).
+  v16i acc[2][PW_XB];  // [weight tile][pixel block]
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < PW_XB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+  const int lane_off = 16 * (lane >> 5) + kq * KSTEP;
+  int dlt[PW_XB];
+  uint32_t vm[PW_XB];
+#pragma unroll
+  for (int j = 0; j < PW_XB; ++j) {
+    const int n = nw + 32 * j + (lane & 31);
+    const bool n_ok = n < (int)a.N;
+    int oh = 0, ow = 0;
+    const int f0 = base_index(n_ok ? n : n0, oh, ow);
+    const int kw_lo = max(0, pad - ow * S), kw_hi = min(KW - 1, W - 1 + pad - ow * S);
+    const int kh_lo = max(0, pad - oh * S), kh_hi = min(KH - 1, H - 1 + pad - oh * S);
+    const uint32_t wbits = kw_hi >= kw_lo ? ((2u << kw_hi) - (1u << kw_lo)) : 0u;  // bits kw_lo..kw_hi
+    uint32_t m = 0;
+#pragma unroll
+    for (int kh = 0; kh < KH; ++kh) m |= (kh >= kh_lo && kh <= kh_hi) ? wbits << (KW * kh) : 0u;
+    vm[j] = n_ok ? m : 0u;
+    dlt[j] = (C + 16) + (f0 - f_lo) * row_stride + lane_off;
+  }
+  const int tap_row_bytes = W * row_stride;
+  // LDS address (from zrow) of the lane's B fragments at tap t (wave-uniform; may be TAPS: nothing valid)
+  auto tap_addr = [&](int t, int j) -> int {
+    const int kh = KW == 1 ? 0 : (t * 11) >> 5;  // t / 3 for t <= 9
+    const int kw = t - kh * KW;
+    const int tapoff = kh * tap_row_bytes + kw * row_stride;
+    return __builtin_amdgcn_sbfe((int)vm[j], t, 1) & (dlt[j] + tapoff);
+  };
+  // the zero-point row, for out-of-image taps
+  {
+    const uint32_t zf = 0x01010101u * (uint32_t)(a.ep.act_zero_point & 15);
+    if (tid < C / 16) *(v4i*)(zrow + tid * 16) = (v4i){(int)zf, (int)zf, (int)zf, (int)zf};
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  RMSMP_PHASE(1);
+
+  // ---- 3. the patch goes to LDS, batch by batch
+#pragma unroll
+  for (int u = 0; u < PW_PATCH_UNROLL; ++u) {
+    const int idx = u * PW_THREADS + tid;
+    if (idx < total) put_piece(idx, pw[u]);
+  }
+#pragma unroll 1
+  for (int base = PW_THREADS * PW_PATCH_UNROLL; base < total; base += PW_THREADS * PW_PATCH_UNROLL) {
+#pragma unroll
+    for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece(pl, base + u * PW_THREADS + tid);
+#pragma unroll
+    for (int u = 0; u < PW_PATCH_UNROLL; ++u) {
+      const int idx = base + u * PW_THREADS + tid;
+      if (idx < total) put_piece(idx, pw[u]);
+    }
+  }
+  // row metadata, field by field: [field][64 rows]
+  if (kq == 0 && wt == 0) {
+    const int ms = (wave / NWT) % MS;
+    int* mf = (int*)(meta + ms * (2 * TILE_M * 16)) + lane;
+    mf[0] = meta_row.x;
+    mf[2 * TILE_M] = meta_row.y;
+    mf[4 * TILE_M] = meta_row.z;
+    mf[6 * TILE_M] = meta_row.w;
+  }
+  // first weight fragments, and the refill of their ring slot
+  v4i av0 = decode_raw<KIND0>(ring0[0], T0);
+  v4i av1 = decode_raw<KIND1>(ring1[0], T1);
+  if (R < NSTEP) {
+    ring0[0] = wide_load<KIND0>(wb0, wl0, R * KS * step0);
+    ring1[0] = wide_load<KIND1>(wb1, wl1, R * KS * step1);
+  }
+
+  __syncthreads();  // patch, zero-point row and row metadata are in LDS
+
+  RMSMP_PHASE(2);
+  // ---- 4. K loop
+  {
+    int cur[PW_XB];
+    v4i b[PW_XB];
+#pragma unroll
+    for (int j = 0; j < PW_XB; ++j) {
+      cur[j] = tap_addr(0, j);
+      b[j] = *(const v4i*)(zrow + cur[j]);
+    }
+    // Software pipeline, one K step = four sub-blocks, one per 32-pixel block j: the two MFMAs of
+    // the block, then word j of both weight fragments of the NEXT step is decoded, then the
+    // block's B fragment is re-read for the next step (its next use is six MFMAs away).  Nothing is
+    // scheduled across sub-blocks, so every LDS read has that distance and the vector
+    // instructions are spread evenly in the shadow of the matrix pipe.
+    constexpr int NV0 = KIND0 == TILE_NIB_SHIFT ? 2 : KIND0 == TILE_NIB_LUT ? 6 : 0;
+    constexpr int NV1 = KIND1 == TILE_NIB_SHIFT ? 2 : KIND1 == TILE_NIB_LUT ? 6 : 0;
+    RMSMP_PHASE(14);
+#pragma unroll 1
+    for (int it = 0; it < NIT; ++it) {
+#ifdef RMSMP_PHASE_TIMING
+      if (it == 1) RMSMP_PHASE(7);
+      if (it == 2) RMSMP_PHASE(10);
+#endif
+      static_for<0, BODY>([&](auto u_tag) {
+        constexpr int u = decltype(u_tag)::value;
+        constexpr bool wraps = u + 1 == BODY;
+        constexpr int slot = (u + 1) % R;
+        constexpr bool new_tap = (u + 1) % SPT == 0;
+        constexpr int boff = ((u + 1) % SPT) * KS * KSTEP;
+        constexpr int NVH = ((NV0 + NV1) * (4 / PW_XB) + (new_tap ? 3 : 0) + 1) / 2;  // vector instructions per MFMA slot
+        // tap of the next step
+        const int t = (it + (wraps ? 1 : 0)) * BT + (wraps ? 0 : (u + 1) / SPT);
+        v4i nav0, nav1;
+        static_for<0, PW_XB>([&](auto j_tag) {
+          constexpr int j = decltype(j_tag)::value;
+          acc[0][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av0, b[j], acc[0][j], 0, 0, 0);
+          acc[1][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av1, b[j], acc[1][j], 0, 0, 0);
+          static_for<0, 4 / PW_XB>([&](auto c_tag) {
+            constexpr int ci = j * (4 / PW_XB) + decltype(c_tag)::value;
+            nav0[ci] = decode_word<KIND0, ci>(ring0[slot], T0);
+            nav1[ci] = decode_word<KIND1, ci>(ring1[slot], T1);
+          });
+          if constexpr (new_tap) cur[j] = tap_addr(t, j);
+          b[j] = *(const v4i*)(zrow + cur[j] + boff);
+          if constexpr (j == PW_XB - 1) {
+            // the ring slot is used up: refill it R steps further on
+            int gs = it * BODY + (u + 1 + R);
+            gs = gs < NSTEP - 1 ? gs : NSTEP - 1;  // past the end: any valid step
+            ring0[slot] = wide_load<KIND0>(wb0, wl0, gs * (KS * step0));
+            ring1[slot] = wide_load<KIND1>(wb1, wl1, gs * (KS * step1));
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x002, NVH, 0);  // VALU
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x002, NVH, 0);  // VALU
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // the LDS read
+          if constexpr (j == PW_XB - 1) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);  // the ring loads
+          __builtin_amdgcn_sched_barrier(0);
+        });
+        av0 = nav0;
+        av1 = nav1;
+#ifdef RMSMP_PHASE_TIMING
+        if (u == 0 && it == 0) RMSMP_PHASE(15);
+#endif
+      });
+    }
+  }
+  RMSMP_PHASE(3);
+
+  // ---- 4. add the KS partial sums of a 64 x 128 block.  Its eight 32x32 blocks (weight tile t,
+  // pixel block j: number 4t + j) are shared out among the KS waves: wave kq finishes blocks
+  // kq*OWN .. kq*OWN+OWN-1 and parks the others in LDS for their owners.  The roles are KS copies
+  // of the code under a wave-uniform branch, so that which accumulators are given and which are
+  // kept is static.
+  constexpr int NBLK = 2 * PW_XB;
+  constexpr int OWN = NBLK / KS;
+  v16i mine[OWN];
+  if constexpr (KS == 1) {
+#pragma unroll
+    for (int q = 0; q < NBLK; ++q) mine[q] = acc[q / PW_XB][q % PW_XB];
+  } else {
+    __syncthreads();  // the exchange buffer overlays the patch: every wave is done reading it
+    const int grp = wave % (NWT * MS);  // which 64 x 128 block of the work-group
+    int* const blk = (int*)xch + grp * (KS * (NBLK - OWN) * 16 * LANES);
+    auto exchange = [&](auto kq_tag) {
+      constexpr int KQ = decltype(kq_tag)::value;
+      {
+        int* dst = blk + KQ * ((NBLK - OWN) * 16 * LANES);
+        int gi = 0;
+#pragma unroll
+        for (int q = 0; q < NBLK; ++q) {
+          if (q / OWN == KQ) continue;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            v4i gq;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) gq[e] = acc[q / PW_XB][q % PW_XB][4 * c + e];
+            *(v4i*)(dst + gi * (16 * LANES) + c * (4 * LANES) + lane * 4) = gq;
+          }
+          ++gi;
+        }
+      }
+      __syncthreads();
+      RMSMP_PHASE(4);
+#pragma unroll
+      for (int o = 0; o < OWN; ++o) {
+        constexpr int q0 = KQ * OWN;
+        const int q = q0 + o;
+        mine[o] = acc[q / PW_XB][q % PW_XB];
+#pragma unroll
+        for (int gk = 0; gk < KS; ++gk) {
+          if (gk == KQ) continue;
+          // where giver gk put block q: its given blocks are all but its own, in order
+          const int gi = q < gk * OWN ? q : q - OWN;
+          const int* src = blk + gk * ((NBLK - OWN) * 16 * LANES) + gi * (16 * LANES);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const v4i got = *(const v4i*)(src + c * (4 * LANES) + lane * 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mine[o][4 * c + e] += got[e];
+          }
+        }
+      }
+    };
+    if (kq == 0)
+      exchange(std::integral_constant<int, 0>{});
+    else if (kq == 1)
+      exchange(std::integral_constant<int, 1>{});
+    else if (KS == 4 && kq == 2)
+      exchange(std::integral_constant<int, KS == 4 ? 2 : 0>{});
+    else if (KS == 4)
+      exchange(std::integral_constant<int, KS == 4 ? 3 : 0>{});
+  }
+  RMSMP_PHASE(5);
+
+  // ---- 5. epilogue: the blocks this wave finishes, tile by tile
+  if (!pair_live) return;
+  const int ms = (wave / NWT) % MS;
+  const int* const meta_pair = (const int*)(meta + ms * (2 * TILE_M * 16));
+  constexpr int TPW = OWN >= PW_XB ? OWN / PW_XB : 1;  // weight tiles this wave finishes
+  constexpr int BPT = OWN / TPW;                        // blocks per such tile
+  constexpr int CH = BPT < 2 ? BPT : 2;                 // finished two at a time (register pressure)
+#pragma unroll
+  for (int ti = 0; ti < TPW; ++ti) {
+    const int q0 = kq * OWN + ti * BPT;  // first block
+    const int my_tile = q0 / PW_XB;
+    if (my_tile == 1 && !two) continue;
+    RowMetaLds rm;
+    rm.base = (const int*)__builtin_assume_aligned(meta_pair + my_tile * TILE_M + 16 * (lane >> 5), 64);
+    rm.rows = 2 * TILE_M;
+    const int n_rows = lane_rows(my_tile ? tr1.nvalid : tr0.nvalid, lane);
+    const int kind = my_tile ? KIND1 : KIND0;
+    const int64_t col0 = (int64_t)nw + 32 * (q0 % PW_XB) + (lane & 31);
+#pragma unroll
+    for (int c0 = 0; c0 < BPT; c0 += CH) {
+      int64_t ncol[CH];
+      v16i blocks[CH];
+#pragma unroll
+      for (int o = 0; o < CH; ++o) {
+        ncol[o] = col0 + 32 * (c0 + o);
+        blocks[o] = mine[ti * BPT + c0 + o];
+      }
+      finish_tiles<CH>(ea, kind, blocks, rm, n_rows, ncol);
+    }
+  }
+  RMSMP_PHASE(6);
+}
+
+template <int TAPS, int CPT, int XB, int KS, int NWT, int MS>
+__device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGeom& g) {
+  RMSMP_PHASE(0);
+  // Work-group id -> (pixel tile bx, row block by).  Consecutive ids go to different XCDs, each
+  // with its own L2, so the gy work-groups that read the same input patch get ids that are equal
+  // modulo 8 and follow each other on that XCD: the patch comes out of memory once, not gy
+  // times.  The grid is padded to a multiple of 8 pixel tiles; the extra work-groups leave.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int by = slot % g.gy;
+  const int bx = (slot / g.gy) * 8 + xcd;
+  if (bx >= g.gx) return;
+  // first of all, the reads of the input patch: they depend on nothing but the pixel tile
+  WidePatchLoads pl;
+  {
+    const int n0 = bx * (32 * XB * NWT);
+    const int hw_out = a.OH * a.OW;
+    const int b = wide_fast_div(n0, g.magic_hw);
+    const int rem = n0 - b * hw_out;
+    const int oh = wide_fast_div(rem, g.magic_ow);
+    const int ow = rem - oh * a.OW;
+    int f_lo = (b * a.d.H + (oh * a.d.stride - a.d.pad)) * a.d.W + (ow * a.d.stride - a.d.pad);
+    f_lo = f_lo < 0 ? 0 : f_lo;
+    const uint32_t x_bytes = (uint32_t)(a.d.B * a.d.H * a.d.W) * (uint32_t)(CPT * KSTEP / 2);
+    pl.f_lo = f_lo;
+    pl.xr = wide_rsrc((const uint8_t*)a.X, x_bytes);
+    pl.src0 = (uint32_t)f_lo * (uint32_t)(CPT * KSTEP / 2);
+    pl.x_last = x_bytes - 16u;
+#pragma unroll
+    for (int u = 0; u < PW_PATCH_UNROLL; ++u) pl.pw[u] = wide_load_piece(pl, u * PW_THREADS + (int)threadIdx.x);
+  }
+  EpArgs ea = pin_epilogue_args(a);
+  ea.stamps = PHASE_LDS_BYTES != 0;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n_pairs = (a.w.n_tiles + 1) / 2;
+  // Pair y is tile y and tile n_tiles-1-y: tiles are sorted by class, so a table-decoded tile is
+  // paired with a cheap one whenever the layer has both.  A wave past the last pair repeats it
+  // (it takes part in every barrier) and stores nothing.
+  int pair = by * MS + (wave / NWT) % MS;
+  const bool pair_live = pair < n_pairs;
+  pair = pair_live ? pair : n_pairs - 1;
+  auto kind_of = [&](int mt) { return mt < a.w.class_tiles[0] ? 0 : mt < a.w.class_tiles[0] + a.w.class_tiles[1] ? 1 : 2; };
+  const int k0 = kind_of(pair), k1 = kind_of(a.w.n_tiles - 1 - pair);
+#define RMSMP_WIDE(K0, K1) \
+  if (k0 == K0 && k1 == K1) wide_wave<TAPS, CPT, XB, KS, NWT, MS, K0, K1>(a, ea, g, bx, pair, pair_live, pl);
+  RMSMP_WIDE(TILE_NIB_SHIFT, TILE_NIB_SHIFT)
+  else RMSMP_WIDE(TILE_NIB_SHIFT, TILE_NIB_LUT)
+  else RMSMP_WIDE(TILE_NIB_SHIFT, TILE_I8)
+  else RMSMP_WIDE(TILE_NIB_LUT, TILE_NIB_LUT)
+  else RMSMP_WIDE(TILE_NIB_LUT, TILE_I8)
+  else RMSMP_WIDE(TILE_I8, TILE_I8)
+#undef RMSMP_WIDE
+  RMSMP_PHASE_FLUSH();
+}
+
+template <int TAPS, int CPT, int XB, int KS, int NWT, int MS>
+__global__ __launch_bounds__(PW_THREADS, 2) void conv_wide_kernel(GemmArgs a, WideGeom g) {
+  wide_kernel_impl<TAPS, CPT, XB, KS, NWT, MS>(a, g);
+}
+
+struct WidePlan {
+  GemmArgs a;  // the argument block (a plain GEMM becomes a 1x1 convolution over N single-pixel images)
+  WideGeom g;
+  size_t lds = 0;
+  unsigned blocks = 0;
+  int xb = 4, ks = 1, nwt = 1, ms = 1;
+};
+
+// Dynamic LDS above 64 KiB must be allowed per kernel once (per device); remember what was set.
+template <int TAPS, int CPT, int XB, int KS, int NWT, int MS>
+inline int launch_wide_t(const WidePlan& p, hipStream_t s) {
+  if constexpr (CPT % KS != 0 || TAPS * (CPT / KS) < 2) {
+    return (int)hipErrorInvalidValue;
+  } else {
+    static bool allowed[64] = {false};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= 64) return (int)hipErrorInvalidDevice;
+    if (!allowed[dev]) {
+      e = hipFuncSetAttribute((const void*)conv_wide_kernel<TAPS, CPT, XB, KS, NWT, MS>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (e != hipSuccess) return (int)e;
+      allowed[dev] = true;
+    }
+    hipLaunchKernelGGL((conv_wide_kernel<TAPS, CPT, XB, KS, NWT, MS>), dim3(p.blocks), dim3(PW_THREADS), p.lds, s, p.a, p.g);
+    return (int)hipGetLastError();
+  }
+}
+
+template <int TAPS, int CPT>
+inline int launch_wide_tc(const WidePlan& p, hipStream_t s) {
+  if (p.xb == 4 && p.ks == 4 && p.nwt == 1 && p.ms == 1) return launch_wide_t<TAPS, CPT, 4, 4, 1, 1>(p, s);
+  if (p.xb == 4 && p.ks == 2 && p.nwt == 2 && p.ms == 1) return launch_wide_t<TAPS, CPT, 4, 2, 2, 1>(p, s);
+  if (p.xb == 4 && p.ks == 1 && p.nwt == 4 && p.ms == 1) return launch_wide_t<TAPS, CPT, 4, 1, 4, 1>(p, s);
+  if (p.xb == 4 && p.ks == 1 && p.nwt == 1 && p.ms == 4) return launch_wide_t<TAPS, CPT, 4, 1, 1, 4>(p, s);
+  if (p.xb == 2 && p.ks == 2 && p.nwt == 2 && p.ms == 1) return launch_wide_t<TAPS, CPT, 2, 2, 2, 1>(p, s);
+  if (p.xb == 2 && p.ks == 4 && p.nwt == 1 && p.ms == 1) return launch_wide_t<TAPS, CPT, 2, 4, 1, 1>(p, s);
+  return (int)hipErrorInvalidValue;
+}
+
+
+}  // namespace rmsmp

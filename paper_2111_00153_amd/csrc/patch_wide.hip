@@ -1,0 +1,175 @@
+// Host side of the wide LDS-resident kernel: which layers it takes, how the four waves of a
+// work-group are shared out, and the dispatch to the per-family launchers (patch_wide_inst.hip).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+
+#include "patch_wide.h"
+
+namespace rmsmp {
+
+#ifndef RMSMP_WIDE_FAMILIES  // (a tuning build may restrict the families it links)
+#define RMSMP_WIDE_FAMILIES(X) X(9, 2) X(9, 4) X(9, 8) X(9, 16) X(1, 2) X(1, 4) X(1, 8) X(1, 16) X(1, 24)
+#endif
+#define RMSMP_WIDE_DECL(TP, CP) int launch_wide_##TP##_##CP(const WidePlan& p, hipStream_t s);
+RMSMP_WIDE_FAMILIES(RMSMP_WIDE_DECL)
+#undef RMSMP_WIDE_DECL
+
+static uint32_t wide_div_magic(int64_t d) {
+  return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + (uint64_t)d - 1) / (uint64_t)d);
+}
+
+
+// One candidate split of the four waves; fills the plan when the layer fits it.
+static bool wide_plan_mode(const GemmArgs& a, int xb, int ks, int nwt, int ms, WidePlan* plan) {
+  const int cpt = a.d.C / KSTEP;
+  if (cpt % ks != 0 || a.d.KH * a.d.KW * (cpt / ks) < 2) return false;
+  const int64_t S = a.d.stride;
+  const int64_t row_extra = S * ((int64_t)a.d.W - a.OW);
+  const int64_t img_extra = (int64_t)a.d.W * ((int64_t)a.d.H - S * a.OH);
+  const int64_t hw = (int64_t)a.OH * a.OW, in_px = (int64_t)a.d.B * a.d.H * a.d.W;
+  const int rs = a.d.C + 16;
+  const int64_t bn = (int64_t)32 * xb * nwt;
+  // widest run of flattened input pixels a tile of bn output pixels touches
+  const int64_t rows_crossed = (bn + a.OW - 1) / a.OW + 1, imgs_crossed = (bn + hw - 1) / hw + 1;
+  const int64_t span = (bn - 1) * S + 1 + (int64_t)(a.d.KH - 1) * a.d.W + (a.d.KW - 1) + rows_crossed * row_extra +
+                       imgs_crossed * (img_extra > 0 ? img_extra : 0);
+  // 32-bit pixel arithmetic and exact one-multiply division in the kernel
+  if ((a.N + bn) * hw >= ((int64_t)1 << 32) || in_px * (a.d.C / 2) >= ((int64_t)1 << 31) || in_px * (a.d.C / 2) < 16) return false;
+  if (in_px + span >= ((int64_t)1 << 31) / rs) return false;
+  // 24-bit LDS address arithmetic
+  const size_t need = (size_t)(span + 1) * rs;  // patch + zero-point row
+  const size_t xch = (size_t)pw_xch_bytes(xb, ks);
+  const size_t lds = PHASE_LDS_BYTES + (size_t)ms * (2 * TILE_M * 16) + (need > xch ? need : xch);
+  if (lds > 160 * 1024) return false;
+  const int n_pairs = (a.w.n_tiles + 1) / 2;
+  const int64_t gx = (a.N + bn - 1) / bn;
+  const int gy = (n_pairs + ms - 1) / ms;
+  if ((gx + 7) / 8 * 8 * gy > 0x7fffffff) return false;
+  plan->a = a;
+  plan->g.gx = (int)gx;
+  plan->g.gy = gy;
+  plan->g.row_stride = rs;
+  plan->g.patch_rows = (int)span;
+  plan->g.magic_hw = wide_div_magic(hw);
+  plan->g.magic_ow = wide_div_magic(a.OW);
+  plan->lds = lds;
+  plan->blocks = (unsigned)((gx + 7) / 8 * 8 * gy);
+  plan->xb = xb;
+  plan->ks = ks;
+  plan->nwt = nwt;
+  plan->ms = ms;
+  return true;
+}
+
+// Channel counts (in K steps of 32) the kernel is instantiated for.
+static bool wide_cpt_supported(int taps, int cpt) {
+  if (taps == 9) return cpt == 2 || cpt == 4 || cpt == 8 || cpt == 16;
+  return cpt == 2 || cpt == 4 || cpt == 8 || cpt == 16 || cpt == 24;
+}
+
+static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
+  if (a0.ep.act_bits != 4) return false;
+  GemmArgs a = a0;
+  if (!a.conv) {
+    if (a.K % (2 * KSTEP) != 0 || a.K > 1024 || a.N >= ((int64_t)1 << 30)) return false;
+    a.conv = 1;
+    a.d = rmsmp_conv_desc{(int32_t)a.N, (int32_t)a.K, 1, 1, 1, 1, 1, 0};
+    a.OH = a.OW = 1;
+  }
+  const int taps = a.d.KH * a.d.KW;
+  if (!(taps == 1 || (a.d.KH == 3 && a.d.KW == 3))) return false;
+  // a strided 1x1 layer would stage stride^2 times the pixels it uses: the general kernel gathers instead
+  if (taps == 1 && a.d.stride > 1) return false;
+  const int cpt = a.d.C / KSTEP;
+  if (a.d.C % KSTEP != 0 || !wide_cpt_supported(taps, cpt)) return false;
+  if (a.w.nks != taps * cpt) return false;
+  // The flattened input index of tap (0,0) must grow with the output pixel number, also across
+  // output rows and images, so that a tile's pixels lie in one contiguous run of the input.
+  const int64_t S = a.d.stride;
+  const int64_t row_extra = S * ((int64_t)a.d.W - a.OW);
+  const int64_t img_extra = (int64_t)a.d.W * ((int64_t)a.d.H - S * a.OH);
+  if (row_extra < 0 || row_extra + img_extra < 0) return false;
+  const int n_pairs = (a.w.n_tiles + 1) / 2;
+  // How the four waves are shared out: the candidate with the lowest estimated time wins.  The
+  // estimate is a per-work-group critical path (cycles, constants fitted to per-phase clock stamps
+  // on an MI355X) times the number of rounds the grid needs: prologue (a fixed part plus the
+  // patch's way through LDS), K loop (cycles per MFMA depend on how many MFMAs share a decoded
+  // weight fragment), partial-sum exchange (LDS traffic), epilogue (per finished 32x32 block).
+  // Work-groups that share a compute unit overlap everything except their K loops' MFMAs.
+  struct Mode { int xb, ks, nwt, ms; };
+  const Mode modes[] = {{4, 1, 1, 4}, {4, 1, 4, 1}, {4, 2, 2, 1}, {4, 4, 1, 1}, {2, 2, 2, 1}, {2, 4, 1, 1}};
+  WidePlan best;
+  double best_cost = 0;
+  bool have = false;
+  for (const Mode& m : modes) {
+    if (m.ms > 1 && n_pairs < m.ms) continue;
+    WidePlan p;
+    if (!wide_plan_mode(a, m.xb, m.ks, m.nwt, m.ms, &p)) continue;
+    const double wgs = (double)p.g.gx * p.g.gy;
+    const double steps = (double)taps * cpt / m.ks;
+    const double mfmas = steps * 2 * m.xb;
+    const double kloop = mfmas * (m.xb == 4 ? 50.0 : 58.0);
+    const double prologue = 3500.0 + (double)p.g.patch_rows * p.g.row_stride / 26.0;
+    const double exchange = m.ks == 1 ? 0.0 : 400.0 + (double)pw_xch_bytes(m.xb, m.ks) / 45.0;
+    const double epilogue = 1800.0 + 670.0 * (2.0 * m.xb / m.ks);
+    const double t_wg = prologue + kloop + exchange + epilogue;
+    const int by_lds = (int)((160 * 1024) / p.lds), by_regs = m.xb == 4 ? 2 : 3;
+    const int k_max = by_lds < by_regs ? by_lds : by_regs;
+    const double per_cu = wgs / 256.0;
+    // what one more work-group on the same compute unit adds: its MFMAs (the matrix pipe is
+    // shared; with 64 pixels per wave the vector ALU is the shared bottleneck instead) and about
+    // a third of everything else
+    const double extra = mfmas * (m.xb == 4 ? 36.0 : 52.0) + 0.35 * (t_wg - kloop);
+    double cost;
+    if (per_cu <= k_max) {
+      const double k = per_cu < 1.0 ? 1.0 : ceil(per_cu);  // the busiest compute unit
+      cost = t_wg + (k - 1.0) * extra;
+    } else {
+      const double rounds = ceil(per_cu / k_max);
+      cost = rounds * (t_wg + (k_max - 1.0) * extra);
+    }
+    if (!have || cost < best_cost) {
+      best = p;
+      best_cost = cost;
+      have = true;
+    }
+  }
+  if (!have) return false;
+  *plan = best;
+  return true;
+}
+
+static int launch_wide(const WidePlan& p, hipStream_t s) {
+  const int taps = p.a.d.KH * p.a.d.KW;
+  const int cpt = p.a.d.C / KSTEP;
+#define RMSMP_WIDE_CASE(TP, CP) \
+  if (taps == TP && cpt == CP) return launch_wide_##TP##_##CP(p, s);
+  RMSMP_WIDE_FAMILIES(RMSMP_WIDE_CASE)
+#undef RMSMP_WIDE_CASE
+  return (int)hipErrorInvalidValue;
+}
+
+// Launches the wide kernel when the layer fits it; *applied says whether it did.
+int try_launch_wide(const GemmArgs& a, void* stream, bool* applied) {
+  WidePlan plan;
+  *applied = wide_kernel_applies(a, &plan);
+#ifdef RMSMP_WIDE_DEV
+  {
+    const char* e = getenv("RMSMP_WIDE");
+    if (e && e[0] == '0') *applied = false;
+    const char* m = getenv("RMSMP_WIDE_MODE");
+    int xb, ks, nwt, ms;
+    if (*applied && m && sscanf(m, "%d,%d,%d,%d", &xb, &ks, &nwt, &ms) == 4) {
+      WidePlan p2;
+      if (wide_plan_mode(plan.a, xb, ks, nwt, ms, &p2)) plan = p2;
+    }
+  }
+#endif
+  if (!*applied) return 0;
+  return launch_wide(plan, (hipStream_t)stream);
+}
+
+}  // namespace rmsmp

@@ -151,6 +151,9 @@ int launch_ste_backward(const SteArgs& a, void* stream);
 
 // Kernel launchers (kernels.hip).  Return hipError_t as int.
 int launch_gemm(const GemmArgs& a, void* stream);
+// LDS-resident implicit-im2col kernel (patch_wide.hip): launches when the layer fits it and says
+// so in *applied.
+int try_launch_wide(const GemmArgs& a, void* stream, bool* applied);
 int launch_im2col(const Im2colArgs& a, void* stream);
 
 }  // namespace rmsmp
