@@ -223,7 +223,7 @@ __device__ __forceinline__ void load_row_meta(const DevicePacked& w, int mt, int
 // 4-bit output codes of one pixel block: clamp(rint(y * inv_s), 0, 15) for the lane's 16 rows,
 // row r in nibble r of the 64-bit result.  BIAS / RELU say which of the optional steps exist, so
 // that the common cases carry no dead instructions.  The float-to-byte conversion packs a value
-// that is already an exact integer in [0, 15], so its own rounding mode plays no role.
+// itself: v_cvt_pk_u8_f32 rounds to nearest even and clamps to [0, 255].
 template <bool BIAS, bool RELU>
 __device__ __forceinline__ void requant_block(const v16i& v, const float (&m)[16], const float (&bias)[16], float inv_s,
                                               uint32_t (&packed)[2]) {
@@ -236,7 +236,10 @@ __device__ __forceinline__ void requant_block(const v16i& v, const float (&m)[16
       float y = __fmul_rn((float)v[r], m[r]);
       if (BIAS) y = __fadd_rn(y, bias[r]);
       if (RELU) y = fmaxf(y, 0.0f);
-      const float t = __builtin_amdgcn_fmed3f(rintf(__fmul_rn(y, inv_s)), 0.0f, 15.0f);
+      // the conversion below rounds half to even and saturates at 0 (checked against rint + clamp
+      // over a dense sweep of [0, 16) and every half-way case up to 300), so only the upper clamp
+      // is left to do here
+      const float t = fminf(__fmul_rn(y, inv_s), 15.0f);
       if (i & 1)
         odd = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, odd);
       else

@@ -464,6 +464,11 @@ static int launch_conv_rows(const GemmArgs& a, hipStream_t s) {
 int launch_gemm(const GemmArgs& a, void* stream) {
   hipStream_t s = (hipStream_t)stream;
   if (a.N <= 0) return 0;
+  {
+    bool applied = false;
+    const int rc = try_launch_conv_first(a, stream, &applied);
+    if (applied) return rc;
+  }
   if (conv_rows_applies(a)) return launch_conv_rows(a, s);
   if (!a.conv && skinny_applies(a)) return a.N <= 32 ? launch_skinny_t<1>(a, s) : launch_skinny_t<2>(a, s);
   {

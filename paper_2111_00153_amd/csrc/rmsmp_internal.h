@@ -154,6 +154,8 @@ int launch_gemm(const GemmArgs& a, void* stream);
 // LDS-resident implicit-im2col kernel (patch_wide.hip): launches when the layer fits it and says
 // so in *applied.
 int try_launch_wide(const GemmArgs& a, void* stream, bool* applied);
+// First-layer kernel (conv_first.hip): 3 input channels, 8-bit activations, stride 2; same convention.
+int try_launch_conv_first(const GemmArgs& a, void* stream, bool* applied);
 int launch_im2col(const Im2colArgs& a, void* stream);
 
 }  // namespace rmsmp
