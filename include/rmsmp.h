@@ -209,6 +209,27 @@ rmsmp_status rmsmp_fake_quant_rows(const float* W, int64_t M, int64_t K, const u
 rmsmp_status rmsmp_ste_backward(const float* W, const float* alpha, const float* dWhat, int64_t M,
                                 int64_t K, float* dW, void* stream);
 
+/*
+ * Test hooks for the kernel dispatch (not part of the method; Section 4 of the paper sizes its
+ * three PE arrays once per device, here the launch shape is picked per layer).
+ *
+ * rmsmp_debug_set_wave_split -- how the four waves of a work-group of the LDS-resident kernel
+ *   are shared out: pixel_blocks (2 or 4: 64 or 128 output pixels per wave), k_split (waves that
+ *   share one output block, each taking every k_split-th K step), side_by_side (output blocks
+ *   next to each other), tile_pairs (pairs of weight tiles per work-group);
+ *   k_split * side_by_side * tile_pairs = 4.  The request applies to every later launch of the
+ *   process where it fits the layer (otherwise the automatic choice stays); all zero returns
+ *   to the automatic choice.  Not synchronized with concurrent launches.
+ * rmsmp_debug_last_dispatch -- what the calling thread's last rmsmp_gemm / rmsmp_conv2d ran:
+ *   out (HOST, 5 entries) = {kernel, pixel_blocks, k_split, side_by_side, tile_pairs} with kernel
+ *   0 none, 1 general, 2 skinny (N <= 64), 3 small-channel rows, 4 first layer (3 channels,
+ *   stride 2), 5 LDS-resident; the other four are 0 unless kernel == 5.
+ * Errors: EINVAL (negative value, NULL).
+ */
+rmsmp_status rmsmp_debug_set_wave_split(int32_t pixel_blocks, int32_t k_split, int32_t side_by_side,
+                                        int32_t tile_pairs);
+rmsmp_status rmsmp_debug_last_dispatch(int32_t out[5]);
+
 #ifdef __cplusplus
 }
 #endif

@@ -53,7 +53,8 @@ _lib = _load()
 EXPORTS = ["rmsmp_last_error", "rmsmp_version", "rmsmp_ratio_counts", "rmsmp_assign_by_variance",
            "rmsmp_pack_weights", "rmsmp_free_packed", "rmsmp_packed_info", "rmsmp_unpack_codes",
            "rmsmp_pack_roundtrip_host", "rmsmp_gemm", "rmsmp_conv2d", "rmsmp_conv2d_workspace_size",
-           "rmsmp_fake_quant_rows", "rmsmp_ste_backward"]
+           "rmsmp_fake_quant_rows", "rmsmp_ste_backward", "rmsmp_debug_set_wave_split",
+           "rmsmp_debug_last_dispatch"]
 
 
 def _check(rc):
@@ -231,6 +232,20 @@ def rmsmp_ste_backward(dWhat, dW, W=None, alpha=None, stream=None):
     M, K = dWhat.shape
     _check(_lib.rmsmp_ste_backward(_dev(W), _dev(alpha), _dev(dWhat), ctypes.c_int64(M), ctypes.c_int64(K),
                                    _dev(dW), _stream(stream)))
+
+
+def rmsmp_debug_set_wave_split(pixel_blocks=0, k_split=0, side_by_side=0, tile_pairs=0):
+    _check(_lib.rmsmp_debug_set_wave_split(int(pixel_blocks), int(k_split), int(side_by_side), int(tile_pairs)))
+
+
+KERNEL_NAMES = ("none", "general", "skinny", "rows", "first_layer", "lds_resident")
+
+
+def rmsmp_debug_last_dispatch():
+    """(kernel name, (pixel_blocks, k_split, side_by_side, tile_pairs)) of this thread's last launch."""
+    out = (ctypes.c_int32 * 5)()
+    _check(_lib.rmsmp_debug_last_dispatch(out))
+    return KERNEL_NAMES[out[0]], tuple(int(v) for v in out[1:])
 
 
 # ---- storage helpers for callers (nibble packing of activation codes; no arithmetic of the method)

@@ -239,6 +239,23 @@ static bool conv_is_implicit(const rmsmp_packed* Wp, const rmsmp_conv_desc* d, i
   return d->C % 16 == 0;
 }
 
+rmsmp_status rmsmp_debug_set_wave_split(int32_t pixel_blocks, int32_t k_split, int32_t side_by_side, int32_t tile_pairs) {
+  if (pixel_blocks < 0 || k_split < 0 || side_by_side < 0 || tile_pairs < 0)
+    return fail(RMSMP_EINVAL, "debug_set_wave_split: negative value");
+  rmsmp::g_forced_split[0] = pixel_blocks;
+  rmsmp::g_forced_split[1] = k_split;
+  rmsmp::g_forced_split[2] = side_by_side;
+  rmsmp::g_forced_split[3] = tile_pairs;
+  return RMSMP_OK;
+}
+
+rmsmp_status rmsmp_debug_last_dispatch(int32_t out[5]) {
+  if (!out) return fail(RMSMP_EINVAL, "debug_last_dispatch: NULL out");
+  const rmsmp::DispatchRecord& r = rmsmp::last_dispatch();
+  out[0] = r.kernel, out[1] = r.xb, out[2] = r.ks, out[3] = r.nwt, out[4] = r.ms;
+  return RMSMP_OK;
+}
+
 rmsmp_status rmsmp_conv2d_workspace_size(const rmsmp_packed* Wp, const rmsmp_conv_desc* d, int32_t act_bits,
                                          size_t* bytes) {
   if (!bytes) return fail(RMSMP_EINVAL, "conv2d_workspace_size: NULL bytes");

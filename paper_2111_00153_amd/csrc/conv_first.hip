@@ -233,9 +233,9 @@ __global__ __launch_bounds__(256, 2) void conv_first_kernel(GemmArgs a, FirstGeo
           nxt = tile_pos(t + 1);
           fetch_units(nxt, raw);
         }
-        // ---- this wave's two blocks (rows 4w .. 4w+3 of the tile)
-#pragma unroll 1
-        for (int bl = 0; bl < 2; ++bl) {
+        // ---- this wave's two blocks (rows 4w .. 4w+3 of the tile); unrolled in the lean 4-bit mode, so
+        // that the second block's LDS reads and MFMAs can be scheduled into the first block's epilogue
+        auto do_block = [&](int bl) {
           const int oh_l = 4 * wave + 2 * bl + pr;
           const uint8_t* fp = buf + (oh_l * 2) * CF_ROWB + (pc + 2 * hh + pos.shift) * 8;
           v4i bf[KHW];
@@ -310,6 +310,13 @@ __global__ __launch_bounds__(256, 2) void conv_first_kernel(GemmArgs a, FirstGeo
               }
             }
           }
+        };
+        if constexpr (MODE == 1) {
+#pragma unroll
+          for (int bl = 0; bl < 2; ++bl) do_block(bl);
+        } else {
+#pragma unroll 1
+          for (int bl = 0; bl < 2; ++bl) do_block(bl);
         }
         // ---- the next tile's pixels go to the other buffer (nobody reads it before the barrier)
         if (more) store_units(nxt, raw, buf0 + (cur ^ 1) * BUF);
@@ -358,6 +365,7 @@ static int launch_conv_first_t(const GemmArgs& a, const FirstGeom& g, unsigned b
 int try_launch_conv_first(const GemmArgs& a, void* stream, bool* applied) {
   *applied = conv_first_applies(a);
   if (!*applied) return 0;
+  last_dispatch() = DispatchRecord{4, 0, 0, 0, 0};
   FirstGeom g;
   g.tiles_w = (a.OW + CF_T - 1) / CF_T;
   g.tiles_h = (a.OH + CF_T - 1) / CF_T;

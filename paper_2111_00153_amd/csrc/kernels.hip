@@ -461,21 +461,35 @@ static int launch_conv_rows(const GemmArgs& a, hipStream_t s) {
   return (int)hipGetLastError();
 }
 
+int g_forced_split[4] = {0, 0, 0, 0};
+DispatchRecord& last_dispatch() {
+  static thread_local DispatchRecord rec;
+  return rec;
+}
+
 int launch_gemm(const GemmArgs& a, void* stream) {
   hipStream_t s = (hipStream_t)stream;
+  last_dispatch() = DispatchRecord{};
   if (a.N <= 0) return 0;
   {
     bool applied = false;
     const int rc = try_launch_conv_first(a, stream, &applied);
     if (applied) return rc;
   }
-  if (conv_rows_applies(a)) return launch_conv_rows(a, s);
-  if (!a.conv && skinny_applies(a)) return a.N <= 32 ? launch_skinny_t<1>(a, s) : launch_skinny_t<2>(a, s);
+  if (conv_rows_applies(a)) {
+    last_dispatch().kernel = 3;
+    return launch_conv_rows(a, s);
+  }
+  if (!a.conv && skinny_applies(a)) {
+    last_dispatch().kernel = 2;
+    return a.N <= 32 ? launch_skinny_t<1>(a, s) : launch_skinny_t<2>(a, s);
+  }
   {
     bool applied = false;
     const int rc = try_launch_wide(a, stream, &applied);
     if (applied) return rc;
   }
+  last_dispatch().kernel = 1;
   if (a.conv) return a.ep.act_bits == 4 ? launch_general<4, true, true>(a, s) : launch_general<8, true, true>(a, s);
   const bool vec = (a.K % 16) == 0;
   if (a.ep.act_bits == 4) return vec ? launch_general<4, false, true>(a, s) : launch_general<4, false, false>(a, s);

@@ -3,8 +3,6 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
-#include <cstdio>
-#include <cstdlib>
 
 #include "patch_wide.h"
 
@@ -24,6 +22,10 @@ static uint32_t wide_div_magic(int64_t d) {
 
 // One candidate split of the four waves; fills the plan when the layer fits it.
 static bool wide_plan_mode(const GemmArgs& a, int xb, int ks, int nwt, int ms, WidePlan* plan) {
+  const bool known = (xb == 4 && ((ks == 4 && nwt == 1 && ms == 1) || (ks == 2 && nwt == 2 && ms == 1) ||
+                                 (ks == 1 && nwt == 4 && ms == 1) || (ks == 1 && nwt == 1 && ms == 4))) ||
+                     (xb == 2 && ((ks == 2 && nwt == 2 && ms == 1) || (ks == 4 && nwt == 1 && ms == 1)));
+  if (!known) return false;
   const int cpt = a.d.C / KSTEP;
   if (cpt % ks != 0 || a.d.KH * a.d.KW * (cpt / ks) < 2) return false;
   const int64_t S = a.d.stride;
@@ -156,19 +158,14 @@ static int launch_wide(const WidePlan& p, hipStream_t s) {
 int try_launch_wide(const GemmArgs& a, void* stream, bool* applied) {
   WidePlan plan;
   *applied = wide_kernel_applies(a, &plan);
-#ifdef RMSMP_WIDE_DEV
-  {
-    const char* e = getenv("RMSMP_WIDE");
-    if (e && e[0] == '0') *applied = false;
-    const char* m = getenv("RMSMP_WIDE_MODE");
-    int xb, ks, nwt, ms;
-    if (*applied && m && sscanf(m, "%d,%d,%d,%d", &xb, &ks, &nwt, &ms) == 4) {
-      WidePlan p2;
-      if (wide_plan_mode(plan.a, xb, ks, nwt, ms, &p2)) plan = p2;
-    }
+  if (*applied && g_forced_split[0] > 0) {
+    WidePlan p2;
+    if (wide_plan_mode(plan.a, g_forced_split[0], g_forced_split[1], g_forced_split[2], g_forced_split[3], &p2)) plan = p2;
   }
-#endif
   if (!*applied) return 0;
+  DispatchRecord& rec = last_dispatch();
+  rec.kernel = 5;
+  rec.xb = plan.xb, rec.ks = plan.ks, rec.nwt = plan.nwt, rec.ms = plan.ms;
   return launch_wide(plan, (hipStream_t)stream);
 }
 

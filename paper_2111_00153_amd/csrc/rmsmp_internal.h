@@ -149,6 +149,16 @@ struct SteArgs {
 int launch_fake_quant_rows(const FakeQuantArgs& a, void* stream);
 int launch_ste_backward(const SteArgs& a, void* stream);
 
+// Test hooks.  g_forced_split: a wave split {pixel blocks per wave, K split, 128-pixel blocks, tile
+// pairs} the LDS-resident kernel should use where it fits the layer (all zero: automatic).
+// last_dispatch(): which kernel the calling thread's last launch_gemm went to.
+struct DispatchRecord {
+  int kernel = 0;  // 0 none, 1 general, 2 skinny, 3 small-channel rows, 4 first layer, 5 LDS-resident
+  int xb = 0, ks = 0, nwt = 0, ms = 0;
+};
+extern int g_forced_split[4];
+DispatchRecord& last_dispatch();
+
 // Kernel launchers (kernels.hip).  Return hipError_t as int.
 int launch_gemm(const GemmArgs& a, void* stream);
 // LDS-resident implicit-im2col kernel (patch_wide.hip): launches when the layer fits it and says
