@@ -32,6 +32,7 @@ struct WideGeom {
   int gx, gy;         // pixel tiles, row blocks (the launch grid is one-dimensional)
   int row_stride;     // LDS bytes per patch pixel (C + 16)
   int patch_rows;     // pixels staged per work-group
+  int gather;         // 1: strided 1x1 layer, only the pixels that are used are staged (one per output pixel)
   uint32_t magic_hw;  // ceil(2^32 / (OH*OW)), 0 when OH*OW == 1
   uint32_t magic_ow;  // ceil(2^32 / OW), 0 when OW == 1
 };
@@ -94,11 +95,25 @@ struct WidePatchLoads {
   uint32_t src0;              // byte offset of the patch in it
   uint32_t x_last;            // last valid 16-byte read
   int f_lo;                   // first staged pixel
+  // strided 1x1 layers (gather): piece idx belongs to output pixel n0 + idx / pieces-per-pixel
+  int gather, n0, n_last, hw_out, OW, H, W, S;
+  uint32_t magic_hw, magic_ow;
 };
 
 // 16-byte piece idx of the patch; reads past the end of X are clamped (those rows are never used)
+template <int PIECES>
 __device__ __forceinline__ uint4 wide_load_piece(const WidePatchLoads& pl, int idx) {
   uint32_t off = pl.src0 + (uint32_t)idx * 16u;
+  if (pl.gather) {
+    const int q = idx / PIECES, piece = idx - q * PIECES;
+    int n = pl.n0 + q;
+    n = n < pl.n_last ? n : pl.n_last;
+    const int b = wide_fast_div(n, pl.magic_hw);
+    const int rem = n - b * pl.hw_out;
+    const int oh = wide_fast_div(rem, pl.magic_ow);
+    const int ow = rem - oh * pl.OW;
+    off = (uint32_t)((b * pl.H + oh * pl.S) * pl.W + ow * pl.S) * (uint32_t)(PIECES * 16) + (uint32_t)piece * 16u;
+  }
   off = off < pl.x_last ? off : pl.x_last;
   const v4w w = __builtin_amdgcn_raw_buffer_load_b128(pl.xr, (int)off, 0, 0);
   return make_uint4(w.x, w.y, w.z, w.w);
@@ -225,7 +240,7 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
 #pragma unroll
     for (int kh = 0; kh < KH; ++kh) m |= (kh >= kh_lo && kh <= kh_hi) ? wbits << (KW * kh) : 0u;
     vm[j] = n_ok ? m : 0u;
-    dlt[j] = (C + 16) + (f0 - f_lo) * row_stride + lane_off;
+    dlt[j] = (C + 16) + (g.gather ? (n_ok ? n - n0 : 0) : f0 - f_lo) * row_stride + lane_off;
   }
   const int tap_row_bytes = W * row_stride;
   // LDS address (from zrow) of the lane's B fragments at tap t (wave-uniform; may be TAPS: nothing valid)
@@ -252,7 +267,7 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
 #pragma unroll 1
   for (int base = PW_THREADS * PW_PATCH_UNROLL; base < total; base += PW_THREADS * PW_PATCH_UNROLL) {
 #pragma unroll
-    for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece(pl, base + u * PW_THREADS + tid);
+    for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece<PIECES>(pl, base + u * PW_THREADS + tid);
 #pragma unroll
     for (int u = 0; u < PW_PATCH_UNROLL; ++u) {
       const int idx = base + u * PW_THREADS + tid;
@@ -474,8 +489,11 @@ __device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGe
     pl.xr = wide_rsrc((const uint8_t*)a.X, x_bytes);
     pl.src0 = (uint32_t)f_lo * (uint32_t)(CPT * KSTEP / 2);
     pl.x_last = x_bytes - 16u;
+    pl.gather = g.gather, pl.n0 = n0, pl.n_last = (int)a.N - 1, pl.hw_out = hw_out, pl.OW = a.OW;
+    pl.H = a.d.H, pl.W = a.d.W, pl.S = a.d.stride, pl.magic_hw = g.magic_hw, pl.magic_ow = g.magic_ow;
+    if (g.gather) pl.f_lo = 0;
 #pragma unroll
-    for (int u = 0; u < PW_PATCH_UNROLL; ++u) pl.pw[u] = wide_load_piece(pl, u * PW_THREADS + (int)threadIdx.x);
+    for (int u = 0; u < PW_PATCH_UNROLL; ++u) pl.pw[u] = wide_load_piece<CPT>(pl, u * PW_THREADS + (int)threadIdx.x);
   }
   EpArgs ea = pin_epilogue_args(a);
   ea.stamps = PHASE_LDS_BYTES != 0;
@@ -544,6 +562,8 @@ inline int launch_wide_tc(const WidePlan& p, hipStream_t s) {
   if (p.xb == 4 && p.ks == 1 && p.nwt == 1 && p.ms == 4) return launch_wide_t<TAPS, CPT, 4, 1, 1, 4>(p, s);
   if (p.xb == 2 && p.ks == 2 && p.nwt == 2 && p.ms == 1) return launch_wide_t<TAPS, CPT, 2, 2, 2, 1>(p, s);
   if (p.xb == 2 && p.ks == 4 && p.nwt == 1 && p.ms == 1) return launch_wide_t<TAPS, CPT, 2, 4, 1, 1>(p, s);
+  if (p.xb == 2 && p.ks == 1 && p.nwt == 1 && p.ms == 4) return launch_wide_t<TAPS, CPT, 2, 1, 1, 4>(p, s);
+  if (p.xb == 2 && p.ks == 1 && p.nwt == 4 && p.ms == 1) return launch_wide_t<TAPS, CPT, 2, 1, 4, 1>(p, s);
   return (int)hipErrorInvalidValue;
 }
 

@@ -24,7 +24,8 @@ static uint32_t wide_div_magic(int64_t d) {
 static bool wide_plan_mode(const GemmArgs& a, int xb, int ks, int nwt, int ms, WidePlan* plan) {
   const bool known = (xb == 4 && ((ks == 4 && nwt == 1 && ms == 1) || (ks == 2 && nwt == 2 && ms == 1) ||
                                  (ks == 1 && nwt == 4 && ms == 1) || (ks == 1 && nwt == 1 && ms == 4))) ||
-                     (xb == 2 && ((ks == 2 && nwt == 2 && ms == 1) || (ks == 4 && nwt == 1 && ms == 1)));
+                     (xb == 2 && ((ks == 2 && nwt == 2 && ms == 1) || (ks == 4 && nwt == 1 && ms == 1) ||
+                                 (ks == 1 && nwt == 1 && ms == 4) || (ks == 1 && nwt == 4 && ms == 1)));
   if (!known) return false;
   const int cpt = a.d.C / KSTEP;
   if (cpt % ks != 0 || a.d.KH * a.d.KW * (cpt / ks) < 2) return false;
@@ -36,7 +37,8 @@ static bool wide_plan_mode(const GemmArgs& a, int xb, int ks, int nwt, int ms, W
   const int64_t bn = (int64_t)32 * xb * nwt;
   // widest run of flattened input pixels a tile of bn output pixels touches
   const int64_t rows_crossed = (bn + a.OW - 1) / a.OW + 1, imgs_crossed = (bn + hw - 1) / hw + 1;
-  const int64_t span = (bn - 1) * S + 1 + (int64_t)(a.d.KH - 1) * a.d.W + (a.d.KW - 1) + rows_crossed * row_extra +
+  const bool gather = a.d.KH * a.d.KW == 1 && a.d.stride > 1;
+  const int64_t span = gather ? bn : (bn - 1) * S + 1 + (int64_t)(a.d.KH - 1) * a.d.W + (a.d.KW - 1) + rows_crossed * row_extra +
                        imgs_crossed * (img_extra > 0 ? img_extra : 0);
   // 32-bit pixel arithmetic and exact one-multiply division in the kernel
   if ((a.N + bn) * hw >= ((int64_t)1 << 32) || in_px * (a.d.C / 2) >= ((int64_t)1 << 31) || in_px * (a.d.C / 2) < 16) return false;
@@ -55,6 +57,7 @@ static bool wide_plan_mode(const GemmArgs& a, int xb, int ks, int nwt, int ms, W
   plan->g.gy = gy;
   plan->g.row_stride = rs;
   plan->g.patch_rows = (int)span;
+  plan->g.gather = gather ? 1 : 0;
   plan->g.magic_hw = wide_div_magic(hw);
   plan->g.magic_ow = wide_div_magic(a.OW);
   plan->lds = lds;
@@ -83,8 +86,9 @@ static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
   }
   const int taps = a.d.KH * a.d.KW;
   if (!(taps == 1 || (a.d.KH == 3 && a.d.KW == 3))) return false;
-  // a strided 1x1 layer would stage stride^2 times the pixels it uses: the general kernel gathers instead
-  if (taps == 1 && a.d.stride > 1) return false;
+  // a strided 1x1 layer stages only the pixels it uses (one per output pixel); padding would need
+  // out-of-image pixels there
+  if (taps == 1 && a.d.stride > 1 && a.d.pad != 0) return false;
   const int cpt = a.d.C / KSTEP;
   if (a.d.C % KSTEP != 0 || !wide_cpt_supported(taps, cpt)) return false;
   if (a.w.nks != taps * cpt) return false;
@@ -102,7 +106,7 @@ static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
   // weight fragment), partial-sum exchange (LDS traffic), epilogue (per finished 32x32 block).
   // Work-groups that share a compute unit overlap everything except their K loops' MFMAs.
   struct Mode { int xb, ks, nwt, ms; };
-  const Mode modes[] = {{4, 1, 1, 4}, {4, 1, 4, 1}, {4, 2, 2, 1}, {4, 4, 1, 1}, {2, 2, 2, 1}, {2, 4, 1, 1}};
+  const Mode modes[] = {{4, 1, 1, 4}, {4, 1, 4, 1}, {4, 2, 2, 1}, {4, 4, 1, 1}, {2, 2, 2, 1}, {2, 4, 1, 1}, {2, 1, 1, 4}, {2, 1, 4, 1}};
   WidePlan best;
   double best_cost = 0;
   bool have = false;
@@ -114,7 +118,7 @@ static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
     const double steps = (double)taps * cpt / m.ks;
     const double mfmas = steps * 2 * m.xb;
     const double kloop = mfmas * (m.xb == 4 ? 50.0 : 58.0);
-    const double prologue = 3500.0 + (double)p.g.patch_rows * p.g.row_stride / 26.0;
+    const double prologue = 1300.0 + (double)p.g.patch_rows * p.g.row_stride / 15.7;
     const double exchange = m.ks == 1 ? 0.0 : 400.0 + (double)pw_xch_bytes(m.xb, m.ks) / 45.0;
     const double epilogue = 1800.0 + 670.0 * (2.0 * m.xb / m.ks);
     const double t_wg = prologue + kloop + exchange + epilogue;
@@ -122,17 +126,14 @@ static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
     const int k_max = by_lds < by_regs ? by_lds : by_regs;
     const double per_cu = wgs / 256.0;
     // what one more work-group on the same compute unit adds: its MFMAs (the matrix pipe is
-    // shared; with 64 pixels per wave the vector ALU is the shared bottleneck instead) and about
-    // a third of everything else
-    const double extra = mfmas * (m.xb == 4 ? 36.0 : 52.0) + 0.35 * (t_wg - kloop);
-    double cost;
-    if (per_cu <= k_max) {
-      const double k = per_cu < 1.0 ? 1.0 : ceil(per_cu);  // the busiest compute unit
-      cost = t_wg + (k - 1.0) * extra;
-    } else {
-      const double rounds = ceil(per_cu / k_max);
-      cost = rounds * (t_wg + (k_max - 1.0) * extra);
-    }
+    // shared) and about a third of everything else; with 64 pixels per wave the vector ALU is the
+    // shared bottleneck throughout, and little of the rest overlaps
+    const double extra = m.xb == 4 ? mfmas * 36.0 + 0.35 * (t_wg - kloop) : mfmas * 52.0 + 0.7 * (t_wg - kloop);
+    // the busiest compute units get n work-groups (a few stragglers beyond a whole number do not
+    // count): whole rounds of k_max sharing the unit, then the rest
+    const int n = per_cu < 1.0 ? 1 : (int)ceil(per_cu - 0.15);
+    const int full = n / k_max, rest = n % k_max;
+    const double cost = full * (t_wg + (k_max - 1) * extra) + (rest > 0 ? t_wg + (rest - 1) * extra : 0.0);
     if (!have || cost < best_cost) {
       best = p;
       best_cost = cost;
