@@ -27,6 +27,11 @@ namespace rmsmp {
 
 constexpr int PW_THREADS = 256;
 constexpr int PW_PATCH_UNROLL = 6;  // 16-byte patch pieces in flight per thread
+// Row metadata of a tile pair in LDS, field by field [field][64 rows]: rowscale bits, rowsum, original
+// row, grouped position, and two values formed once per work-group for the lean 4-bit epilogue: the
+// row's multiplier rowscale * activation scale (* 1/16 for shift-decoded tiles) and zero point * rowsum
+// (* 16 for those tiles).
+constexpr int PW_META_BYTES = 2 * TILE_M * 24;
 
 struct WideGeom {
   int gx, gy;         // pixel tiles, row blocks (the launch grid is one-dimensional)
@@ -159,7 +164,7 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
   // LDS: row metadata [MS pairs][4 fields][64 rows] | zero-point row (C bytes, +16 pad) | decoded
   // input patch.  The exchange buffer later lies over the zero-point row and the patch.
   uint8_t* const meta = smem_raw + PHASE_LDS_BYTES;
-  uint8_t* const zrow = meta + MS * (2 * TILE_M * 16);
+  uint8_t* const zrow = meta + MS * PW_META_BYTES;
   uint8_t* const patch = zrow + (C + 16);
   uint8_t* const xch = zrow;
 
@@ -277,11 +282,14 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
   // row metadata, field by field: [field][64 rows]
   if (kq == 0 && wt == 0) {
     const int ms = (wave / NWT) % MS;
-    int* mf = (int*)(meta + ms * (2 * TILE_M * 16)) + lane;
+    int* mf = (int*)(meta + ms * PW_META_BYTES) + lane;
     mf[0] = meta_row.x;
     mf[2 * TILE_M] = meta_row.y;
     mf[4 * TILE_M] = meta_row.z;
     mf[6 * TILE_M] = meta_row.w;
+    const bool x16 = (lane < TILE_M ? KIND0 : KIND1) == TILE_NIB_SHIFT;
+    mf[8 * TILE_M] = __float_as_int(__fmul_rn(__fmul_rn(__int_as_float(meta_row.x), ea.act_scale), x16 ? 0.0625f : 1.0f));
+    mf[10 * TILE_M] = (x16 ? 16 * ea.zp : ea.zp) * meta_row.y;
   }
   // first weight fragments, and the refill of their ring slot
   v4i av0 = decode_raw<KIND0>(ring0[0], T0);
@@ -432,10 +440,16 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
   // ---- 5. epilogue: the blocks this wave finishes, tile by tile
   if (!pair_live) return;
   const int ms = (wave / NWT) % MS;
-  const int* const meta_pair = (const int*)(meta + ms * (2 * TILE_M * 16));
+  const int* const meta_pair = (const int*)(meta + ms * PW_META_BYTES);
   constexpr int TPW = OWN >= PW_XB ? OWN / PW_XB : 1;  // weight tiles this wave finishes
   constexpr int BPT = OWN / TPW;                        // blocks per such tile
   constexpr int CH = BPT < 2 ? BPT : 2;                 // finished two at a time (register pressure)
+  // The common case gets an epilogue of its own, chosen once per wave: 4-bit output, no bias, no
+  // ReLU beyond the clamp at code 0 (a positive output scale makes the two the same), the whole
+  // layer a multiple of 16 rows and the output 8-byte aligned.  Everything else goes through the
+  // general finish_tiles.
+  const bool lean = ea.out_kind == 2 && ea.bias == nullptr && !(ea.relu != 0 && !(ea.out_inv_scale > 0.0f)) &&
+                    (ea.M & 15) == 0 && (((uintptr_t)ea.Y) & 7) == 0;
 #pragma unroll
   for (int ti = 0; ti < TPW; ++ti) {
     const int q0 = kq * OWN + ti * BPT;  // first block
@@ -447,6 +461,42 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
     const int n_rows = lane_rows(my_tile ? tr1.nvalid : tr0.nvalid, lane);
     const int kind = my_tile ? KIND1 : KIND0;
     const int64_t col0 = (int64_t)nw + 32 * (q0 % PW_XB) + (lane & 31);
+    if (lean) {
+      // 4-bit codes, no bias, no separate ReLU, all 16 rows of the lane alive: multipliers and
+      // zero-point terms come ready from LDS, a pixel's 16 codes leave as one 8-byte store
+      if (n_rows == 16) {
+        float mrow[16], dummy[16];
+        int crow[16];
+        const float4* mp = (const float4*)(rm.base + 4 * (2 * TILE_M));
+        const int4* cp = (const int4*)(rm.base + 5 * (2 * TILE_M));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float4 mv = mp[q];
+          mrow[4 * q] = mv.x, mrow[4 * q + 1] = mv.y, mrow[4 * q + 2] = mv.z, mrow[4 * q + 3] = mv.w;
+        }
+        if (ea.zp != 0) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int4 cv = cp[q];
+            crow[4 * q] = cv.x, crow[4 * q + 1] = cv.y, crow[4 * q + 2] = cv.z, crow[4 * q + 3] = cv.w;
+          }
+        }
+        RMSMP_GLOBAL uint8_t* const out0 = as_global((uint8_t*)ea.Y) + (rm.gpos0() >> 1);
+#pragma unroll
+        for (int o = 0; o < BPT; ++o) {
+          v16i v = mine[ti * BPT + o];
+          if (ea.zp != 0) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) v[r] -= crow[r];
+          }
+          uint32_t packed[2];
+          requant_block<false, false>(v, mrow, dummy, ea.out_inv_scale, packed);
+          const int64_t n = col0 + 32 * o;
+          if (n < ea.N) *(RMSMP_GLOBAL v2u*)(out0 + n * (ea.M / 2)) = (v2u){packed[0], packed[1]};
+        }
+      }
+      continue;
+    }
 #pragma unroll
     for (int c0 = 0; c0 < BPT; c0 += CH) {
       int64_t ncol[CH];

@@ -46,7 +46,7 @@ static bool wide_plan_mode(const GemmArgs& a, int xb, int ks, int nwt, int ms, W
   // 24-bit LDS address arithmetic
   const size_t need = (size_t)(span + 1) * rs;  // patch + zero-point row
   const size_t xch = (size_t)pw_xch_bytes(xb, ks);
-  const size_t lds = PHASE_LDS_BYTES + (size_t)ms * (2 * TILE_M * 16) + (need > xch ? need : xch);
+  const size_t lds = PHASE_LDS_BYTES + (size_t)ms * PW_META_BYTES + (need > xch ? need : xch);
   if (lds > 160 * 1024) return false;
   const int n_pairs = (a.w.n_tiles + 1) / 2;
   const int64_t gx = (a.N + bn - 1) / bn;
