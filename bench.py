@@ -20,9 +20,9 @@ sys.path.insert(0, ROOT)
 INT8_MFMA_PEAK_TOPS = 5000.0  # MI355X dense int8, published
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the timed kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a
-# 256 MiB device copy (profiles/conv_patch_kernel_configs1.md); a counter reading cannot be taken from
+# 256 MiB device copy (profiles/conv_wide_kernel_configs1.md); a counter reading cannot be taken from
 # inside this script, so the last measured value is carried here.
-MEASURED_TRAFFIC_BYTES = 5423369
+MEASURED_TRAFFIC_BYTES = 5114236
 
 
 def make_conv_workload(cfg_id=1):
@@ -39,22 +39,25 @@ def make_conv_workload(cfg_id=1):
     return dict(cfg=c, W=W, scheme=scheme, x=x, counts=counts, K=K)
 
 
-def cpu_baseline(wl, n_images=2):
-    """The oracle, as it stands, on the first n_images of the same workload."""
+def cpu_baseline(wl, repeats=3):
+    """The oracle, as it stands, on the whole batch of the same workload, `repeats` times over
+    (about 20 core-seconds on 16 host threads)."""
     import oracle
     c = wl["cfg"]
     ref = oracle.quantize_rows(wl["W"], wl["scheme"])
-    d = oracle.conv_desc(n_images, c["C"], c["H"], c["W"], c["KH"], c["KW"], c["stride"], c["pad"])
-    x = wl["x"][:n_images].astype(np.int32)
+    d = oracle.conv_desc(c["B"], c["C"], c["H"], c["W"], c["KH"], c["KW"], c["stride"], c["pad"])
+    x = wl["x"].astype(np.int32)
     wint = ref["wint"].reshape(c["M"], c["C"], c["KH"], c["KW"])
     rs = oracle.rowsum(ref["wint"])
     t0 = time.perf_counter()
-    acc = oracle.conv_acc(wint, x, d, 0)
-    _, y, _ = oracle.epilogue(acc, rs, 0, ref["rowscale"], c["s_x"], None, True)
+    for _ in range(repeats):
+        acc = oracle.conv_acc(wint, x, d, 0)
+        _, y, _ = oracle.epilogue(acc, rs, 0, ref["rowscale"], c["s_x"], None, True)
     t1 = time.perf_counter()
-    ops = 2.0 * c["M"] * wl["K"] * acc.shape[1]
+    ops = 2.0 * c["M"] * wl["K"] * acc.shape[1] * repeats
     return dict(value=ops / (t1 - t0) / 1e12, unit="TOPS", cores=oracle.num_threads(), kind="oracle",
-                sample="first %d of %d images of the same layer (%.3f s)" % (n_images, c["B"], t1 - t0)), ref, y
+                sample="all %d images of the same layer, %d passes (%.2f s wall on %d threads)"
+                       % (c["B"], repeats, t1 - t0, oracle.num_threads())), ref, y
 
 
 def main():
@@ -117,6 +120,8 @@ def main():
     tops = ops / (ms_per_step * 1e-3) / 1e12
     kern_ms = gpu_ms / args.steps
     achieved = ops / (kern_ms * 1e-3) / 1e12
+    kernel, split = rm.rmsmp_debug_last_dispatch()
+    kernel_name = ("rmsmp::conv_wide_kernel<9, 8, %d, %d, %d, %d>" % split) if kernel == "lds_resident" else kernel
 
     if base is not None:
         # spot check of the timed configuration against the oracle (first images)
@@ -144,7 +149,7 @@ def main():
                    "rows_per_scheme": list(wl["counts"])},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES,
-                     "kernel": "rmsmp::conv_patch_kernel<9, 8>", "avg_launch_us": round(kern_ms * 1e3, 3)},
+                     "kernel": kernel_name, "avg_launch_us": round(kern_ms * 1e3, 3)},
         "cpu_baseline": base,
     }
     if args.calibrate_copy:
