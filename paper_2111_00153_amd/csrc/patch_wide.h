@@ -1,21 +1,35 @@
-// Wide LDS-resident implicit-im2col kernel of librmsmp (gfx950).
+// LDS-resident implicit-im2col kernel of librmsmp (gfx950): 1x1 and 3x3 layers of any stride with
+// 64 to 512 input channels, and plain GEMMs with K up to 768 taken as 1x1 layers.
 //
-// Same data flow as the narrower LDS-resident kernel -- the input pixels a work-group needs are
-// read once, decoded to int8 and kept in LDS for all taps; packed weights stream from global
-// memory through a register ring and are decoded in registers -- with two changes that the
-// measurements asked for:
+// The input pixels a work-group needs -- one contiguous run of the flattened NHWC tensor (strided
+// 1x1 layers: exactly the pixels used, gathered) -- are read from memory once, decoded to int8
+// and kept in LDS for all taps: implicit im2col, nothing is materialised, and a pixel is reused
+// nine times from LDS.  Out-of-image taps read a row that holds the zero-point code.  Packed
+// weights stream from global memory (buffer loads: descriptor and K offset in scalar registers)
+// through a register ring a few K steps ahead of their use and are decoded in registers; the two
+// weight tiles of a wave are tile y and tile (count-1-y), so a table-decoded (PoT) tile is paired
+// with a cheap one whenever the layer has both.
 //
-//  * A wave owns 64 rows x 128 pixels (two weight fragments x four activation fragments, eight
-//    MFMAs per K step).  The decode of a weight fragment is vector-ALU work that shares the issue
-//    port with the MFMAs: at 64 pixels per wave a Fixed-4 + PoT-4 tile pair needs ~8 vector
-//    instructions per MFMA (more than fit under one), at 128 pixels ~4.
-//  * The K loop is a real loop (one filter row, or one tap, per iteration) instead of
-//    straight-line code for all of K.  A kernel starts with a cold instruction cache; code that is
-//    executed once is fetched at memory latency, a loop body is fetched once.
+// What the measurements asked for:
+//  * The decode of a weight fragment is vector-ALU work and shares the issue port with the MFMAs.
+//    A wave that owns 64 rows x 128 pixels (two weight fragments x four activation fragments,
+//    eight MFMAs per K step) spends ~4 vector instructions per MFMA on a Fixed-4 + PoT-4 pair, at
+//    64 pixels per wave ~8 (more than fit under one MFMA).  Both sizes exist (XB = 4 / 2): the
+//    smaller one gives the grid more work-groups and lets three of them share a compute unit.
+//  * The K loop is a real loop (one filter row, or one tap, per iteration) whose steps are cut in
+//    sub-blocks "two MFMAs, a slice of next step's decode, one LDS read" that the scheduler may not
+//    mix: every LDS read then has six MFMAs between issue and use, and the vector instructions sit
+//    evenly in the shadow of the matrix pipe (40 cycles per MFMA in steady state, 32 = peak).
+//  * A launch of the sizes at hand is one round of work-groups, so its time is one work-group's
+//    critical path: every global read that needs only the kernel arguments is issued before
+//    anything else (the patch before the code of the tile classes is even fetched), accumulator
+//    zeroing and address arithmetic run in the shadow of those reads, and the common 4-bit output
+//    has an epilogue of its own whose per-row constants were formed in the prologue.
 //
-// The four waves of a work-group are shared out over K quarters (KS), 128-pixel blocks (NWT) and
-// tile pairs (MS), KS*NWT*MS = 4: small grids split K four ways, wide layers put the waves side
-// by side, layers with many rows give every wave its own tile pair against the same patch.
+// The four waves of a work-group are shared out over K parts (KS, partial sums added through
+// LDS), pixel blocks side by side (NWT) and tile pairs (MS), KS*NWT*MS = 4: small grids split K,
+// wide layers put the waves side by side, layers with many rows give every wave its own tile pair
+// against the same patch.  The host picks the split per layer from a small cost model.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -144,10 +158,8 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
   constexpr int BODY = BT * SPT;
   constexpr int NIT = TAPS / BT;
   // ring depth: a divisor of the body, so that a step's ring slot is the same in every iteration
-#ifndef RMSMP_WIDE_RING
-#define RMSMP_WIDE_RING 4
-#endif
-  constexpr int R = BODY % RMSMP_WIDE_RING == 0 ? RMSMP_WIDE_RING : BODY % 4 == 0 ? 4 : BODY % 3 == 0 ? 3 : BODY % 2 == 0 ? 2 : 1;
+  // (a ring of six steps measured no faster than four)
+  constexpr int R = BODY % 4 == 0 ? 4 : BODY % 3 == 0 ? 3 : BODY % 2 == 0 ? 2 : 1;
   static_assert(R <= NSTEP, "ring deeper than the K loop");
 
   const int tid = threadIdx.x;
