@@ -8,16 +8,25 @@
 //  * Nothing is lowered.  Weights are stored one K step per filter row (element (kh, kw, c) at
 //    kh*32 + kw*4 + c), so a lane's B fragment for filter row kh is four consecutive input pixels
 //    (padded to four bytes each) of input row 2*oh - pad + kh.
-//  * A work-group walks through several 16x16 tiles of output pixels with the weights of two
-//    weight tiles held in registers the whole time (the narrower kernel fetched them again for
-//    every 128 pixels: 14 KiB per wave against 0.4 KiB of input).
+//  * A work-group walks through several 16x16 tiles of output pixels; each wave holds the weights
+//    of one weight tile in registers the whole time and takes half of the rows of every pixel
+//    tile (the narrower kernel fetched the weights again for every 128 pixels: 14 KiB per wave
+//    against 0.4 KiB of input).  Three work-groups share a compute unit; the launch has exactly
+//    768 of them when there are that many tiles, with the tiles spread evenly, so every compute
+//    unit carries the same load in a single round.
 //  * The input pixels of a tile are staged in LDS already in MFMA operand order: the staging
 //    thread reads 16 aligned bytes (four pixels), and seven vector instructions turn them into the
-//    16 bytes two fragments will read, so the inner loop has no byte shuffles at all.
+//    16 bytes two fragments will read, so the inner loop has no byte shuffles at all.  Tiles whose
+//    staged columns lie inside the image skip the padding masks.
 //  * The next tile's input is fetched while the current tile is multiplied, and written to the
-//    other LDS buffer afterwards: one barrier per tile.
-//  * Per-row multipliers (rowscale * activation scale) and biases are formed once per work-group
-//    and read from LDS by the 4-bit epilogue.
+//    other LDS buffer afterwards: one barrier per tile.  A pass issues all its loads (first tile,
+//    packed weights, row metadata) before it waits for any of them.
+//  * The kernel is bound by vector instructions (a wave's vector instruction costs 4 to 5 cycles
+//    of its SIMD, and the 4-bit epilogue needs five per output value: convert, two roundings of
+//    the scale product, clamp, pack), so the common case has a loop of its own (template
+//    parameter chosen by the host) that carries nothing else: row multipliers in registers, the
+//    four blocks of a tile in one piece of straight-line code, 4-bit codes stored through a
+//    buffer descriptor whose per-lane offset is fixed for the pass.
 #include <hip/hip_runtime.h>
 
 #include "device_common.h"
@@ -32,7 +41,7 @@ constexpr int CF_MAX_TILES = 64;  // row metadata of all weight tiles sits in LD
 struct FirstGeom {
   int tiles_w, tiles_h;   // 16x16 output tiles per image
   int total_tiles;        // B * tiles_h * tiles_w
-  int tiles_per_wg;
+  int tiles_base, tiles_rem;  // work-group i takes tiles_base tiles, one more when i < tiles_rem
   uint32_t magic_tw;      // ceil(2^32 / tiles_w), 0 when tiles_w == 1
   uint32_t magic_thw;     // ceil(2^32 / (tiles_w * tiles_h)), 0 when that is 1
 };
@@ -43,8 +52,8 @@ __device__ __forceinline__ int cf_fast_div(int n, uint32_t magic) {
 
 typedef unsigned cf_v4w __attribute__((ext_vector_type(4)));
 
-template <int KHW>
-__global__ __launch_bounds__(256, 2) void conv_first_kernel(GemmArgs a, FirstGeom g) {
+template <int KHW, int MODE_>
+__global__ __launch_bounds__(256, 3) void conv_first_kernel(GemmArgs a, FirstGeom g) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
   constexpr int PH = 2 * (CF_T - 1) + KHW;   // staged input rows per tile
   constexpr int BUF = PH * CF_ROWB;          // bytes per staging buffer
@@ -61,22 +70,10 @@ __global__ __launch_bounds__(256, 2) void conv_first_kernel(GemmArgs a, FirstGeo
   float* const mtab = (float*)(meta + a.w.n_tiles * (4 * TILE_M));
   float* const btab = mtab + a.w.n_tiles * TILE_M;
 
-  const int t_lo = blockIdx.x * g.tiles_per_wg;
-  const int t_hi = min(t_lo + g.tiles_per_wg, g.total_tiles);
+  const int wg = blockIdx.x;
+  const int t_lo = wg * g.tiles_base + min(wg, g.tiles_rem);
+  const int t_hi = t_lo + g.tiles_base + (wg < g.tiles_rem ? 1 : 0);
   if (t_lo >= t_hi) return;
-
-  // ---- row metadata of every weight tile, field by field
-  for (int idx = tid; idx < a.w.n_tiles * TILE_M; idx += 256) {
-    const int4 m = ((const int4*)a.w.p_meta)[idx];
-    int* dst = meta + (idx / TILE_M) * (4 * TILE_M) + (idx % TILE_M);
-    dst[0] = m.x;
-    dst[TILE_M] = m.y;
-    dst[2 * TILE_M] = m.z;
-    dst[3 * TILE_M] = m.w;
-    const float fold = tile_ref(a.w, idx / TILE_M).kind == TILE_NIB_SHIFT ? 0.0625f : 1.0f;
-    mtab[idx] = __fmul_rn(__fmul_rn(__int_as_float(m.x), ea.act_scale), fold);
-    btab[idx] = ea.bias ? as_global(ea.bias)[m.z < 0 ? 0 : m.z] : 0.0f;
-  }
 
   const uint32_t x_bytes = (uint32_t)(a.d.B * H * W) * 3u;
   const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc((void*)a.X, 0, (int)x_bytes, 0x00020000);
@@ -144,6 +141,12 @@ __global__ __launch_bounds__(256, 2) void conv_first_kernel(GemmArgs a, FirstGeo
       uint32_t B0 = __builtin_amdgcn_perm(f, e, 0x0c040c01u);  // a1 0  b1 0
       uint32_t A1 = __builtin_amdgcn_perm(h, f, 0x07050402u);  // c0 c2 d0 d2
       uint32_t B1 = __builtin_amdgcn_perm(h, f, 0x0c060c03u);  // c1 0  d1 0
+      // a tile whose staged columns all lie inside the image, with zero point 0: nothing to mask
+      // (rows outside the image were fetched as zeros)
+      if (z == 0 && p.iw_s + 1 >= 0 && p.iw_s + 1 + 4 * CF_UNITS <= W) {
+        *(v4i*)(buf + r * CF_ROWB + u * 16) = (v4i){(int)A0, (int)B0, (int)A1, (int)B1};
+        continue;
+      }
       // pixels outside the image hold the zero point
       const uint32_t va = (row_ok && iw >= 0 && iw < W) ? 0x0000ffffu : 0u;
       const uint32_t vb = (row_ok && iw + 1 >= 0 && iw + 1 < W) ? 0xffff0000u : 0u;
@@ -158,68 +161,100 @@ __global__ __launch_bounds__(256, 2) void conv_first_kernel(GemmArgs a, FirstGeo
     }
   };
 
+  // ---- row metadata of every weight tile, field by field
+  auto stage_metadata = [&]() {
+  for (int idx = tid; idx < a.w.n_tiles * TILE_M; idx += 256) {
+    const int4 m = ((const int4*)a.w.p_meta)[idx];
+    int* dst = meta + (idx / TILE_M) * (4 * TILE_M) + (idx % TILE_M);
+    dst[0] = m.x;
+    dst[TILE_M] = m.y;
+    dst[2 * TILE_M] = m.z;
+    dst[3 * TILE_M] = m.w;
+    const float fold = tile_ref(a.w, idx / TILE_M).kind == TILE_NIB_SHIFT ? 0.0625f : 1.0f;
+    mtab[idx] = __fmul_rn(__fmul_rn(__int_as_float(m.x), ea.act_scale), fold);
+    btab[idx] = ea.bias ? as_global(ea.bias)[m.z < 0 ? 0 : m.z] : 0.0f;
+  }
+  };
+
   // this lane's output pixel inside a 2-row x 16-column block, and its fragment offset in a staged row
   const int pr = (lane & 31) >> 4, pc = lane & 15, hh = lane >> 5;
 
-  // ---- weight tiles two at a time; all pixel tiles of the work-group against them
+  // ---- weight tiles two at a time; all pixel tiles of the work-group against them.  A wave
+  // holds the weights of ONE tile (even waves the first of the two, odd waves the second) and
+  // takes half of a pixel tile's rows: few registers per wave, so that four work-groups share a
+  // compute unit and hide each other's LDS, MFMA and store latencies.
+  const TilePos pos0 = tile_pos(t_lo);
 #pragma unroll 1
   for (int mt0 = 0; mt0 < a.w.n_tiles; mt0 += 2) {
-    const bool two = mt0 + 1 < a.w.n_tiles;
-    const int mt1 = two ? mt0 + 1 : mt0;
-    const TileRef tr0 = tile_ref(a.w, mt0), tr1 = tile_ref(a.w, mt1);
-    // decoded weight fragments of the KHW filter rows, kept for all pixel tiles
-    v4i av[2][KHW];
-    auto load_weights = [&](const TileRef& tr, int mt, v4i (&dst)[KHW]) {
+    const bool mine_live = mt0 + (wave & 1) < a.w.n_tiles;
+    const int mt = mine_live ? mt0 + (wave & 1) : mt0;
+    const TileRef tr = tile_ref(a.w, mt);
+    // All loads of the pass are issued before anything waits: the first pixel tile, the packed
+    // weight fragments of the KHW filter rows and (first pass) the row metadata.
+    cf_v4w raw0[UPT];
+    fetch_units(pos0, raw0);
+    uint4 wr[KHW];
+    uint4 T = make_uint4(0, 0, 0, 0);
+    {
       const uint8_t* wp = a.w.blob + tr.blob_off;
       if (tr.kind == TILE_I8) {
 #pragma unroll
-        for (int kh = 0; kh < KHW; ++kh)
-          dst[kh] = decode_raw<TILE_I8>(load_raw<TILE_I8>(wp, (uint32_t)(kh * LANES + lane) * 16), make_uint4(0, 0, 0, 0));
-      } else if (tr.kind == TILE_NIB_SHIFT) {
-#pragma unroll
-        for (int kh = 0; kh < KHW; ++kh)
-          dst[kh] = decode_raw<TILE_NIB_SHIFT>(load_raw<TILE_NIB_SHIFT>(wp, (uint32_t)(kh * LANES + lane) * 8), make_uint4(0, 0, 0, 0));
+        for (int kh = 0; kh < KHW; ++kh) wr[kh] = load_raw<TILE_I8>(wp, (uint32_t)(kh * LANES + lane) * 16);
       } else {
-        const uint4 T = *(const uint4*)(a.w.p_lut + ((int64_t)mt * TILE_M + tile_row_goff(lane & 31)) * 4);
 #pragma unroll
-        for (int kh = 0; kh < KHW; ++kh)
-          dst[kh] = decode_raw<TILE_NIB_LUT>(load_raw<TILE_NIB_LUT>(wp, (uint32_t)(kh * LANES + lane) * 8), T);
+        for (int kh = 0; kh < KHW; ++kh) {
+          const uint2 v = load_raw<TILE_NIB_SHIFT>(wp, (uint32_t)(kh * LANES + lane) * 8);
+          wr[kh] = make_uint4(v.x, v.y, 0, 0);
+        }
+        if (tr.kind == TILE_NIB_LUT) T = *(const uint4*)(a.w.p_lut + ((int64_t)mt * TILE_M + tile_row_goff(lane & 31)) * 4);
       }
-    };
-    load_weights(tr0, mt0, av[0]);
-    load_weights(tr1, mt1, av[1]);
-
-    // first pixel tile
-    TilePos pos = tile_pos(t_lo);
-    {
-      cf_v4w raw[UPT];
-      fetch_units(pos, raw);
-      __syncthreads();  // metadata stored / previous pass done with both buffers
-      store_units(pos, raw, buf0);
     }
+    if (mt0 == 0) stage_metadata();
+    // decoded weight fragments, kept for all pixel tiles
+    v4i av[KHW];
+    if (tr.kind == TILE_I8) {
+#pragma unroll
+      for (int kh = 0; kh < KHW; ++kh) av[kh] = decode_raw<TILE_I8>(wr[kh], T);
+    } else if (tr.kind == TILE_NIB_SHIFT) {
+#pragma unroll
+      for (int kh = 0; kh < KHW; ++kh) av[kh] = decode_raw<TILE_NIB_SHIFT>(make_uint2(wr[kh].x, wr[kh].y), T);
+    } else {
+#pragma unroll
+      for (int kh = 0; kh < KHW; ++kh) av[kh] = decode_raw<TILE_NIB_LUT>(make_uint2(wr[kh].x, wr[kh].y), T);
+    }
+    // (decoded once: the fragments stay in registers, not re-derived from the packed words per tile)
+#pragma unroll
+    for (int kh = 0; kh < KHW; ++kh) asm volatile("" : "+v"(av[kh]));
+    TilePos pos = pos0;
+    __syncthreads();  // metadata stored / previous pass done with both buffers
+    store_units(pos0, raw0, buf0);
     __syncthreads();
 
-    int gpos0[2], n_rows[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int mt = t ? mt1 : mt0;
-      const TileRef& tr = t ? tr1 : tr0;
-      n_rows[t] = lane_rows(tr.nvalid, lane);
-      gpos0[t] = meta[mt * (4 * TILE_M) + 16 * hh + 3 * TILE_M];
-    }
-    if (!two) n_rows[1] = 0;
+    const int n_rows = mine_live ? lane_rows(tr.nvalid, lane) : 0;
+    const int gpos0 = meta[mt * (4 * TILE_M) + 16 * hh + 3 * TILE_M];
     // a lane's 16 codes of a pixel leave as one 8-byte store when all 16 rows exist and the place is aligned
     const int64_t row_bytes = ea.M / 2;
-    bool whole[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-      whole[t] = n_rows[t] == 16 && (row_bytes & 7) == 0 && ((((uintptr_t)ea.Y) + (gpos0[t] >> 1)) & 7) == 0;
+    const bool whole = n_rows == 16 && (row_bytes & 7) == 0 && ((((uintptr_t)ea.Y) + (gpos0 >> 1)) & 7) == 0;
+    // 4-bit output as a buffer (only used when it is below 2 GiB, see the choice of the loop below)
+    const __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc((void*)ea.Y, 0, (int)(ea.N * row_bytes), 0x00020000);
+    const int s_row = a.OW * (int)row_bytes;
+    const int lane_off = (pr * a.OW + pc) * (int)row_bytes + (gpos0 >> 1);
 
-    // The pixel-tile loop exists three times, chosen once per work-group, so that the common
+    // The pixel-tile loop exists three times (kernel template parameter, chosen by the host), so that the common
     // 4-bit-output case carries neither the other output kinds nor the optional steps:
     // MODE 1: 4-bit output, zero point 0, no bias, no separate ReLU (with a positive output scale the
     //         clamp at code 0 does what ReLU would); MODE 2: 4-bit output, zero point 0, anything
     //         else; MODE 0: every other epilogue, through the general finish_tiles.
+    // the lean loop keeps its 16 row multipliers in registers
+    float mkeep[16];
+    {
+      const float4* mp = (const float4*)(mtab + mt * TILE_M + 16 * hh);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 mv = mp[q];
+        mkeep[4 * q] = mv.x, mkeep[4 * q + 1] = mv.y, mkeep[4 * q + 2] = mv.z, mkeep[4 * q + 3] = mv.w;
+      }
+    }
     auto run_tiles = [&](auto mode_tag) {
       constexpr int MODE = decltype(mode_tag)::value;
 #pragma unroll 1
@@ -233,10 +268,11 @@ __global__ __launch_bounds__(256, 2) void conv_first_kernel(GemmArgs a, FirstGeo
           nxt = tile_pos(t + 1);
           fetch_units(nxt, raw);
         }
-        // ---- this wave's two blocks (rows 4w .. 4w+3 of the tile); unrolled in the lean 4-bit mode, so
-        // that the second block's LDS reads and MFMAs can be scheduled into the first block's epilogue
-        auto do_block = [&](int bl) {
-          const int oh_l = 4 * wave + 2 * bl + pr;
+        const int s_tile = ((pos.b * a.OH + pos.oh0) * a.OW + pos.ow0) * (int)row_bytes;  // (used by 4-bit stores only)
+        const bool col_ok = pos.ow0 + pc < a.OW;
+        // ---- this wave's four blocks (rows 8*(w/2) .. 8*(w/2)+7 of the tile) against its weight tile
+        auto do_block = [&](const int bl) {
+          const int oh_l = 8 * (wave >> 1) + 2 * bl + pr;
           const uint8_t* fp = buf + (oh_l * 2) * CF_ROWB + (pc + 2 * hh + pos.shift) * 8;
           v4i bf[KHW];
 #pragma unroll
@@ -245,78 +281,79 @@ __global__ __launch_bounds__(256, 2) void conv_first_kernel(GemmArgs a, FirstGeo
             const uint2 hi = *(const uint2*)(fp + kh * CF_ROWB + 8);
             bf[kh] = (v4i){(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
           }
-          v16i acc[2][1];
+          v16i acc[1];
 #pragma unroll
-          for (int i = 0; i < 2; ++i)
+          for (int r = 0; r < 16; ++r) acc[0][r] = 0;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][0][r] = 0;
-#pragma unroll
-          for (int kh = 0; kh < KHW; ++kh) {
-            acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av[0][kh], bf[kh], acc[0][0], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av[1][kh], bf[kh], acc[1][0], 0, 0, 0);
-          }
+          for (int kh = 0; kh < KHW; ++kh) acc[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av[kh], bf[kh], acc[0], 0, 0, 0);
           const int oh = pos.oh0 + oh_l, ow = pos.ow0 + pc;
           const bool px_ok = oh < a.OH && ow < a.OW;
           const int64_t n = px_ok ? ((int64_t)pos.b * a.OH + oh) * a.OW + ow : a.N;  // a.N = no store
-          RMSMP_GLOBAL uint8_t* const out_px = as_global((uint8_t*)ea.Y) + n * row_bytes;
-#pragma unroll
-          for (int ti = 0; ti < 2; ++ti) {
-            if (n_rows[ti] <= 0) continue;
-            if constexpr (MODE == 0) {
-              RowMetaLds rm;
-              rm.base = (const int*)__builtin_assume_aligned(meta + (ti ? mt1 : mt0) * (4 * TILE_M) + 16 * hh, 64);
-              rm.rows = TILE_M;
-              const int64_t ncol[1] = {n};
-              finish_tiles<1>(ea, (ti ? tr1 : tr0).kind, acc[ti], rm, n_rows[ti], ncol);
+          if constexpr (MODE == 0) {
+            RowMetaLds rm;
+            rm.base = (const int*)__builtin_assume_aligned(meta + mt * (4 * TILE_M) + 16 * hh, 64);
+            rm.rows = TILE_M;
+            const int64_t ncol[1] = {n};
+            finish_tiles<1>(ea, tr.kind, acc, rm, n_rows, ncol);
+          } else {
+            uint32_t packed[2];
+            float brow[16];
+            const int row0 = mt * TILE_M + 16 * hh;
+            if constexpr (MODE == 1) {
+              requant_block<false, false>(acc[0], mkeep, brow, ea.out_inv_scale, packed);
             } else {
-              uint32_t packed[2];
-              float mrow[16], brow[16];
-              const int row0 = (ti ? mt1 : mt0) * TILE_M + 16 * hh;
+              float mrow[16];
               const float4* mp = (const float4*)(mtab + row0);
 #pragma unroll
               for (int q = 0; q < 4; ++q) {
                 const float4 mv = mp[q];
                 mrow[4 * q] = mv.x, mrow[4 * q + 1] = mv.y, mrow[4 * q + 2] = mv.z, mrow[4 * q + 3] = mv.w;
               }
-              if constexpr (MODE == 1) {
-                requant_block<false, false>(acc[ti][0], mrow, brow, ea.out_inv_scale, packed);
-              } else {
-                const float4* bp = (const float4*)(btab + row0);
+              const float4* bp = (const float4*)(btab + row0);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                  const float4 bv = bp[q];  // zeros when there is no bias
-                  brow[4 * q] = bv.x, brow[4 * q + 1] = bv.y, brow[4 * q + 2] = bv.z, brow[4 * q + 3] = bv.w;
-                }
-                const bool relu_q = ea.relu != 0 && !(ea.out_inv_scale > 0.0f);
-                if (ea.bias) {
-                  if (relu_q)
-                    requant_block<true, true>(acc[ti][0], mrow, brow, ea.out_inv_scale, packed);
-                  else
-                    requant_block<true, false>(acc[ti][0], mrow, brow, ea.out_inv_scale, packed);
-                } else {
-                  if (relu_q)
-                    requant_block<false, true>(acc[ti][0], mrow, brow, ea.out_inv_scale, packed);
-                  else
-                    requant_block<false, false>(acc[ti][0], mrow, brow, ea.out_inv_scale, packed);
-                }
+              for (int q = 0; q < 4; ++q) {
+                const float4 bv = bp[q];  // zeros when there is no bias
+                brow[4 * q] = bv.x, brow[4 * q + 1] = bv.y, brow[4 * q + 2] = bv.z, brow[4 * q + 3] = bv.w;
               }
-              if (px_ok) {
-                RMSMP_GLOBAL uint8_t* dst = out_px + (gpos0[ti] >> 1);
-                if (whole[ti]) {
-                  *(RMSMP_GLOBAL v2u*)dst = (v2u){packed[0], packed[1]};
-                } else {
-                  for (int b = 0; b < n_rows[ti] / 2; ++b) dst[b] = (uint8_t)(packed[b >> 2] >> (8 * (b & 3)));
-                }
+              const bool relu_q = ea.relu != 0 && !(ea.out_inv_scale > 0.0f);
+              if (ea.bias) {
+                if (relu_q)
+                  requant_block<true, true>(acc[0], mrow, brow, ea.out_inv_scale, packed);
+                else
+                  requant_block<true, false>(acc[0], mrow, brow, ea.out_inv_scale, packed);
+              } else {
+                if (relu_q)
+                  requant_block<false, true>(acc[0], mrow, brow, ea.out_inv_scale, packed);
+                else
+                  requant_block<false, false>(acc[0], mrow, brow, ea.out_inv_scale, packed);
               }
+            }
+            if (MODE == 1 || whole) {
+              // per-lane part of the address fixed for the whole pass, the rest scalar; pixels outside
+              // the output get an offset beyond the buffer and are dropped
+              const int s_off = s_tile + (8 * (wave >> 1) + 2 * bl) * s_row;
+              __builtin_amdgcn_raw_buffer_store_b64((v2u){packed[0], packed[1]}, yr, (col_ok && oh < a.OH) ? lane_off : (int)0x80000000, s_off, 0);
+            } else if (px_ok) {
+              RMSMP_GLOBAL uint8_t* dst = as_global((uint8_t*)ea.Y) + n * row_bytes + (gpos0 >> 1);
+              for (int b = 0; b < n_rows / 2; ++b) dst[b] = (uint8_t)(packed[b >> 2] >> (8 * (b & 3)));
             }
           }
         };
+        // (mine_live is the same for the whole wave: every lane feeds the MFMAs)
         if constexpr (MODE == 1) {
+          // all four blocks in one piece of straight-line code: the LDS reads, MFMAs and requantization
+          // of different blocks overlap, and the number of stores in flight is known where the next
+          // tile's pixels are waited for
+          if (mine_live) {
 #pragma unroll
-          for (int bl = 0; bl < 2; ++bl) do_block(bl);
+            for (int bl = 0; bl < 4; ++bl) do_block(bl);
+          }
         } else {
 #pragma unroll 1
-          for (int bl = 0; bl < 2; ++bl) do_block(bl);
+          for (int bl = 0; bl < 4; ++bl) {
+            if (!mine_live) break;
+            do_block(bl);
+          }
         }
         // ---- the next tile's pixels go to the other buffer (nobody reads it before the barrier)
         if (more) store_units(nxt, raw, buf0 + (cur ^ 1) * BUF);
@@ -324,14 +361,7 @@ __global__ __launch_bounds__(256, 2) void conv_first_kernel(GemmArgs a, FirstGeo
         __syncthreads();
       }
     };
-    const bool u4_plain = ea.out_kind == 2 && ea.zp == 0;
-    const bool no_extras = ea.bias == nullptr && !(ea.relu != 0 && !(ea.out_inv_scale > 0.0f));
-    if (u4_plain && no_extras)
-      run_tiles(std::integral_constant<int, 1>{});
-    else if (u4_plain)
-      run_tiles(std::integral_constant<int, 2>{});
-    else
-      run_tiles(std::integral_constant<int, 0>{});
+    run_tiles(std::integral_constant<int, MODE_>{});
   }
 }
 
@@ -357,7 +387,18 @@ template <int KHW>
 static int launch_conv_first_t(const GemmArgs& a, const FirstGeom& g, unsigned blocks, hipStream_t s) {
   constexpr int PH = 2 * (CF_T - 1) + KHW;
   const size_t lds = (size_t)2 * PH * CF_ROWB + (size_t)a.w.n_tiles * TILE_M * (16 + 8);  // at most 12 + 48 KiB
-  hipLaunchKernelGGL(conv_first_kernel<KHW>, dim3(blocks), dim3(256), lds, s, a, g);
+  // which of the three pixel-tile loops the launch needs (see the kernel)
+  const int64_t row_bytes = a.M / 2;
+  const bool relu_step = a.ep.relu != 0 && !(a.ep.out_inv_scale > 0.0f);
+  const bool u4_plain = a.ep.out_kind == 2 && a.ep.act_zero_point == 0 && a.N * row_bytes < ((int64_t)1 << 31);
+  // every lane of the lean loop stores 16 whole codes: full weight tiles, 8-byte aligned places
+  const bool all_whole = a.M % TILE_M == 0 && (((uintptr_t)a.Y) & 7) == 0;
+  if (u4_plain && a.ep.bias == nullptr && !relu_step && all_whole)
+    hipLaunchKernelGGL((conv_first_kernel<KHW, 1>), dim3(blocks), dim3(256), lds, s, a, g);
+  else if (u4_plain)
+    hipLaunchKernelGGL((conv_first_kernel<KHW, 2>), dim3(blocks), dim3(256), lds, s, a, g);
+  else
+    hipLaunchKernelGGL((conv_first_kernel<KHW, 0>), dim3(blocks), dim3(256), lds, s, a, g);
   return (int)hipGetLastError();
 }
 
@@ -370,13 +411,15 @@ int try_launch_conv_first(const GemmArgs& a, void* stream, bool* applied) {
   g.tiles_w = (a.OW + CF_T - 1) / CF_T;
   g.tiles_h = (a.OH + CF_T - 1) / CF_T;
   g.total_tiles = a.d.B * g.tiles_w * g.tiles_h;
-  // two work-groups share a compute unit: aim at one round of 512, each with several tiles to
-  // spread the weight fetch over
-  int per = (g.total_tiles + 511) / 512;
-  g.tiles_per_wg = per < 1 ? 1 : per;
+  // Three work-groups share a compute unit (register budget): exactly that many work-groups when
+  // there are enough tiles, the tiles spread evenly over them, so that every compute unit carries
+  // the same load in one round and a work-group spreads its weight fetch over several tiles.
+  int n_wg = g.total_tiles < 768 ? g.total_tiles : 768;
+  g.tiles_base = g.total_tiles / n_wg;
+  g.tiles_rem = g.total_tiles % n_wg;
   g.magic_tw = cf_div_magic(g.tiles_w);
   g.magic_thw = cf_div_magic((int64_t)g.tiles_w * g.tiles_h);
-  const unsigned blocks = (unsigned)((g.total_tiles + g.tiles_per_wg - 1) / g.tiles_per_wg);
+  const unsigned blocks = (unsigned)n_wg;
   hipStream_t s = (hipStream_t)stream;
   switch (a.d.KH) {
     case 3: return launch_conv_first_t<3>(a, g, blocks, s);

@@ -154,6 +154,15 @@ def test_first_layer_kernel(rm, oracle, geom, M, ratio):
     _check_conv(rm, oracle, geom, M, ratio, 8, 0, False, False, 23, "first_layer")
 
 
+@pytest.mark.parametrize("B,k,pad", [(40, 7, 3), (17, 3, 1)])
+def test_first_layer_kernel_several_tiles_per_work_group(rm, oracle, B, k, pad):
+    """More 16x16 pixel tiles than work-groups (the launch has at most 768): work-groups walk through
+    two or three tiles with double-buffered staging, and the tile counts differ by one between them."""
+    geom = (B, 3, 224, 224, k, k, 2, pad)
+    _check_conv(rm, oracle, geom, 64, (0, 0, 100), 8, 0, False, True, 31, "first_layer")
+    _check_conv(rm, oracle, geom, 40, (35, 60, 5), 8, 2, True, True, 32, "first_layer")
+
+
 def test_dispatch_record_names_the_kernel(rm, oracle):
     """The dispatch hook reports the kernel family of the last launch on this thread."""
     rng = np.random.default_rng(5)
