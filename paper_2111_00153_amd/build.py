@@ -12,6 +12,8 @@ HEADERS = ["csrc/rmsmp_internal.h", "csrc/device_common.h", "csrc/patch_wide.h",
 # (filter taps, channels / 32) families of the wide LDS-resident kernel: csrc/patch_wide_inst.hip is
 # compiled once per family so that they build in parallel
 WIDE_FAMILIES = [(9, 2), (9, 4), (9, 8), (9, 16), (1, 2), (1, 4), (1, 8), (1, 16), (1, 24)]
+# channel counts (in K steps) whose 1x1 family also exists as the variant that stages a deeper layer in parts
+WIDE_DEEP_FAMILIES = [16, 24]
 WIDE_SOURCE = "csrc/patch_wide_inst.hip"
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -26,6 +28,9 @@ def _units():
     for taps, cpt in WIDE_FAMILIES:
         units.append((WIDE_SOURCE, ["-DRMSMP_WIDE_TAPS=%d" % taps, "-DRMSMP_WIDE_CPT=%d" % cpt],
                       os.path.join(OBJ_DIR, "patch_wide_inst_%d_%d.o" % (taps, cpt))))
+    for cpt in WIDE_DEEP_FAMILIES:
+        units.append((WIDE_SOURCE, ["-DRMSMP_WIDE_TAPS=1", "-DRMSMP_WIDE_CPT=%d" % cpt, "-DRMSMP_WIDE_DEEP=1"],
+                      os.path.join(OBJ_DIR, "patch_wide_inst_deep_%d.o" % cpt)))
     return units
 
 

@@ -1,5 +1,6 @@
 // LDS-resident implicit-im2col kernel of librmsmp (gfx950): 1x1 and 3x3 layers of any stride with
-// 64 to 512 input channels, and plain GEMMs with K up to 768 taken as 1x1 layers.
+// 64 to 512 input channels, and plain GEMMs taken as 1x1 layers (K up to 768 in one piece, deeper
+// ones staged in parts of 768 or 512 channels by the DEEP variant).
 //
 // The input pixels a work-group needs -- one contiguous run of the flattened NHWC tensor (strided
 // 1x1 layers: exactly the pixels used, gathered) -- are read from memory once, decoded to int8
@@ -11,7 +12,8 @@
 // with a cheap one whenever the layer has both.
 //
 // What the measurements asked for:
-//  * The decode of a weight fragment is vector-ALU work and shares the issue port with the MFMAs.
+//  * The decode of a weight fragment is vector-ALU work (a vector instruction costs a lone wave
+//    about six cycles of its SIMD, an MFMA 32; the two overlap, so a K step takes the larger sum).
 //    A wave that owns 64 rows x 128 pixels (two weight fragments x four activation fragments,
 //    eight MFMAs per K step) spends ~4 vector instructions per MFMA on a Fixed-4 + PoT-4 pair, at
 //    64 pixels per wave ~8 (more than fit under one MFMA).  Both sizes exist (XB = 4 / 2): the
@@ -52,6 +54,8 @@ struct WideGeom {
   int row_stride;     // LDS bytes per patch pixel (C + 16)
   int patch_rows;     // pixels staged per work-group
   int gather;         // 1: strided 1x1 layer, only the pixels that are used are staged (one per output pixel)
+  int nchunk;         // 1x1 layers / GEMMs deeper than one LDS patch: the channels are staged nchunk parts of C, one after the other
+  int pix_bytes;      // bytes of one input pixel in memory (all its channels)
   uint32_t magic_hw;  // ceil(2^32 / (OH*OW)), 0 when OH*OW == 1
   uint32_t magic_ow;  // ceil(2^32 / OW), 0 when OW == 1
 };
@@ -112,6 +116,7 @@ struct WidePatchLoads {
   uint4 pw[PW_PATCH_UNROLL];
   __amdgpu_buffer_rsrc_t xr;  // the activation tensor
   uint32_t src0;              // byte offset of the patch in it
+  int chunked, pix_bytes;     // chunked: a pixel's staged channels are only part of its pix_bytes bytes
   uint32_t x_last;            // last valid 16-byte read
   int f_lo;                   // first staged pixel
   // strided 1x1 layers (gather): piece idx belongs to output pixel n0 + idx / pieces-per-pixel
@@ -133,13 +138,17 @@ __device__ __forceinline__ uint4 wide_load_piece(const WidePatchLoads& pl, int i
     const int ow = rem - oh * pl.OW;
     off = (uint32_t)((b * pl.H + oh * pl.S) * pl.W + ow * pl.S) * (uint32_t)(PIECES * 16) + (uint32_t)piece * 16u;
   }
+  if (pl.chunked) {
+    const int q = idx / PIECES, piece = idx - q * PIECES;
+    off = pl.src0 + (uint32_t)q * (uint32_t)pl.pix_bytes + (uint32_t)piece * 16u;
+  }
   off = off < pl.x_last ? off : pl.x_last;
   const v4w w = __builtin_amdgcn_raw_buffer_load_b128(pl.xr, (int)off, 0, 0);
   return make_uint4(w.x, w.y, w.z, w.w);
 }
 
 // Everything one wave does.  KIND0 / KIND1: storage classes of its two weight tiles.
-template <int TAPS, int CPT, int XB, int KS, int NWT, int MS, int KIND0, int KIND1>
+template <int TAPS, int CPT, int XB, int KS, int NWT, int MS, bool DEEP, int KIND0, int KIND1>
 __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, const WideGeom& g, int bx, int pair,
                                           bool pair_live, WidePatchLoads& pl) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
@@ -197,8 +206,12 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
   // ---- weight stream of this wave: uniform base of its first K step + 32-bit lane offset
   constexpr int fb0 = KIND0 == TILE_I8 ? 16 : 8, fb1 = KIND1 == TILE_I8 ? 16 : 8;
   constexpr int step0 = LANES * fb0, step1 = LANES * fb1;  // bytes per K step
-  const __amdgpu_buffer_rsrc_t wb0 = wide_rsrc(a.w.blob + tr0.blob_off, (uint32_t)(CPT * TAPS) * step0);
-  const __amdgpu_buffer_rsrc_t wb1 = wide_rsrc(a.w.blob + tr1.blob_off, (uint32_t)(CPT * TAPS) * step1);
+  // 1x1 layers deeper than one patch: the K loop runs once per part of the channels (see step 4)
+  static_assert(!DEEP || TAPS == 1, "only 1x1 layers are staged in parts");
+  const int nchunk = DEEP ? g.nchunk : 1;
+  const int last_step = nchunk * NSTEP - 1;
+  const __amdgpu_buffer_rsrc_t wb0 = wide_rsrc(a.w.blob + tr0.blob_off, (uint32_t)(nchunk * CPT * TAPS) * step0);
+  const __amdgpu_buffer_rsrc_t wb1 = wide_rsrc(a.w.blob + tr1.blob_off, (uint32_t)(nchunk * CPT * TAPS) * step1);
   const uint32_t wl0 = (uint32_t)lane * fb0 + kq * step0, wl1 = (uint32_t)lane * fb1 + kq * step1;
   typename RawFrag<KIND0>::type ring0[R];
   typename RawFrag<KIND1>::type ring1[R];
@@ -275,22 +288,25 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
   __builtin_amdgcn_sched_barrier(0);
   RMSMP_PHASE(1);
 
-  // ---- 3. the patch goes to LDS, batch by batch
-#pragma unroll
-  for (int u = 0; u < PW_PATCH_UNROLL; ++u) {
-    const int idx = u * PW_THREADS + tid;
-    if (idx < total) put_piece(idx, pw[u]);
-  }
-#pragma unroll 1
-  for (int base = PW_THREADS * PW_PATCH_UNROLL; base < total; base += PW_THREADS * PW_PATCH_UNROLL) {
-#pragma unroll
-    for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece<PIECES>(pl, base + u * PW_THREADS + tid);
+  // ---- 3. the patch goes to LDS, batch by batch (the first batch is already in registers)
+  auto stage_patch = [&](const int t0) {
 #pragma unroll
     for (int u = 0; u < PW_PATCH_UNROLL; ++u) {
-      const int idx = base + u * PW_THREADS + tid;
+      const int idx = u * PW_THREADS + t0;
       if (idx < total) put_piece(idx, pw[u]);
     }
-  }
+#pragma unroll 1
+    for (int base = PW_THREADS * PW_PATCH_UNROLL; base < total; base += PW_THREADS * PW_PATCH_UNROLL) {
+#pragma unroll
+      for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece<PIECES>(pl, base + u * PW_THREADS + t0);
+#pragma unroll
+      for (int u = 0; u < PW_PATCH_UNROLL; ++u) {
+        const int idx = base + u * PW_THREADS + t0;
+        if (idx < total) put_piece(idx, pw[u]);
+      }
+    }
+  };
+  stage_patch(tid);
   // row metadata, field by field: [field][64 rows]
   if (kq == 0 && wt == 0) {
     const int ms = (wave / NWT) % MS;
@@ -306,7 +322,7 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
   // first weight fragments, and the refill of their ring slot
   v4i av0 = decode_raw<KIND0>(ring0[0], T0);
   v4i av1 = decode_raw<KIND1>(ring1[0], T1);
-  if (R < NSTEP) {
+  if (R <= last_step) {
     ring0[0] = wide_load<KIND0>(wb0, wl0, R * KS * step0);
     ring1[0] = wide_load<KIND1>(wb1, wl1, R * KS * step1);
   }
@@ -315,7 +331,32 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
 
   RMSMP_PHASE(2);
   // ---- 4. K loop
-  {
+#pragma unroll 1
+  for (int ch = 0; ch < nchunk; ++ch) {
+    // The next part of the channels replaces the patch: same pixels, pl.src0 moved on by C/2 bytes.
+    // With 64 pixels per wave there are registers to spare, and the first batch of a part's reads
+    // is issued before the previous part's K loop (PREFETCH); the piece addresses are formed again
+    // for every part rather than kept in registers through the K loop.
+    constexpr bool PREFETCH = DEEP && XB == 2;
+    if (DEEP && ch > 0) {
+      __syncthreads();  // every wave is done with the previous part
+      int t0 = tid;
+      asm volatile("" : "+v"(t0));
+      if constexpr (!PREFETCH) {
+        pl.src0 += C / 2;
+#pragma unroll
+        for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece<PIECES>(pl, u * PW_THREADS + t0);
+      }
+      stage_patch(t0);
+      __syncthreads();
+    }
+    if (PREFETCH && ch + 1 < nchunk) {
+      pl.src0 += C / 2;
+      int t0 = tid;
+      asm volatile("" : "+v"(t0));
+#pragma unroll
+      for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece<PIECES>(pl, u * PW_THREADS + t0);
+    }
     int cur[PW_XB];
     v4i b[PW_XB];
 #pragma unroll
@@ -360,8 +401,8 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
           b[j] = *(const v4i*)(zrow + cur[j] + boff);
           if constexpr (j == PW_XB - 1) {
             // the ring slot is used up: refill it R steps further on
-            int gs = it * BODY + (u + 1 + R);
-            gs = gs < NSTEP - 1 ? gs : NSTEP - 1;  // past the end: any valid step
+            int gs = ch * NSTEP + it * BODY + (u + 1 + R);
+            gs = gs < last_step ? gs : last_step;  // past the end: any valid step
             ring0[slot] = wide_load<KIND0>(wb0, wl0, gs * (KS * step0));
             ring1[slot] = wide_load<KIND1>(wb1, wl1, gs * (KS * step1));
           }
@@ -524,7 +565,7 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
   RMSMP_PHASE(6);
 }
 
-template <int TAPS, int CPT, int XB, int KS, int NWT, int MS>
+template <int TAPS, int CPT, int XB, int KS, int NWT, int MS, bool DEEP>
 __device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGeom& g) {
   RMSMP_PHASE(0);
   // Work-group id -> (pixel tile bx, row block by).  Consecutive ids go to different XCDs, each
@@ -546,10 +587,11 @@ __device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGe
     const int ow = rem - oh * a.OW;
     int f_lo = (b * a.d.H + (oh * a.d.stride - a.d.pad)) * a.d.W + (ow * a.d.stride - a.d.pad);
     f_lo = f_lo < 0 ? 0 : f_lo;
-    const uint32_t x_bytes = (uint32_t)(a.d.B * a.d.H * a.d.W) * (uint32_t)(CPT * KSTEP / 2);
+    const uint32_t x_bytes = (uint32_t)(a.d.B * a.d.H * a.d.W) * (uint32_t)g.pix_bytes;
     pl.f_lo = f_lo;
     pl.xr = wide_rsrc((const uint8_t*)a.X, x_bytes);
-    pl.src0 = (uint32_t)f_lo * (uint32_t)(CPT * KSTEP / 2);
+    pl.src0 = (uint32_t)f_lo * (uint32_t)g.pix_bytes;
+    pl.chunked = DEEP, pl.pix_bytes = g.pix_bytes;
     pl.x_last = x_bytes - 16u;
     pl.gather = g.gather, pl.n0 = n0, pl.n_last = (int)a.N - 1, pl.hw_out = hw_out, pl.OW = a.OW;
     pl.H = a.d.H, pl.W = a.d.W, pl.S = a.d.stride, pl.magic_hw = g.magic_hw, pl.magic_ow = g.magic_ow;
@@ -570,7 +612,7 @@ __device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGe
   auto kind_of = [&](int mt) { return mt < a.w.class_tiles[0] ? 0 : mt < a.w.class_tiles[0] + a.w.class_tiles[1] ? 1 : 2; };
   const int k0 = kind_of(pair), k1 = kind_of(a.w.n_tiles - 1 - pair);
 #define RMSMP_WIDE(K0, K1) \
-  if (k0 == K0 && k1 == K1) wide_wave<TAPS, CPT, XB, KS, NWT, MS, K0, K1>(a, ea, g, bx, pair, pair_live, pl);
+  if (k0 == K0 && k1 == K1) wide_wave<TAPS, CPT, XB, KS, NWT, MS, DEEP, K0, K1>(a, ea, g, bx, pair, pair_live, pl);
   RMSMP_WIDE(TILE_NIB_SHIFT, TILE_NIB_SHIFT)
   else RMSMP_WIDE(TILE_NIB_SHIFT, TILE_NIB_LUT)
   else RMSMP_WIDE(TILE_NIB_SHIFT, TILE_I8)
@@ -581,9 +623,9 @@ __device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGe
   RMSMP_PHASE_FLUSH();
 }
 
-template <int TAPS, int CPT, int XB, int KS, int NWT, int MS>
+template <int TAPS, int CPT, int XB, int KS, int NWT, int MS, bool DEEP>
 __global__ __launch_bounds__(PW_THREADS, 2) void conv_wide_kernel(GemmArgs a, WideGeom g) {
-  wide_kernel_impl<TAPS, CPT, XB, KS, NWT, MS>(a, g);
+  wide_kernel_impl<TAPS, CPT, XB, KS, NWT, MS, DEEP>(a, g);
 }
 
 struct WidePlan {
@@ -592,10 +634,11 @@ struct WidePlan {
   size_t lds = 0;
   unsigned blocks = 0;
   int xb = 4, ks = 1, nwt = 1, ms = 1;
+  int cpt = 0;  // K steps of 32 channels staged at a time (the kernel family)
 };
 
 // Dynamic LDS above 64 KiB must be allowed per kernel once (per device); remember what was set.
-template <int TAPS, int CPT, int XB, int KS, int NWT, int MS>
+template <int TAPS, int CPT, int XB, int KS, int NWT, int MS, bool DEEP>
 inline int launch_wide_t(const WidePlan& p, hipStream_t s) {
   if constexpr (CPT % KS != 0 || TAPS * (CPT / KS) < 2) {
     return (int)hipErrorInvalidValue;
@@ -606,26 +649,26 @@ inline int launch_wide_t(const WidePlan& p, hipStream_t s) {
     if (e != hipSuccess) return (int)e;
     if (dev < 0 || dev >= 64) return (int)hipErrorInvalidDevice;
     if (!allowed[dev]) {
-      e = hipFuncSetAttribute((const void*)conv_wide_kernel<TAPS, CPT, XB, KS, NWT, MS>,
+      e = hipFuncSetAttribute((const void*)conv_wide_kernel<TAPS, CPT, XB, KS, NWT, MS, DEEP>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       if (e != hipSuccess) return (int)e;
       allowed[dev] = true;
     }
-    hipLaunchKernelGGL((conv_wide_kernel<TAPS, CPT, XB, KS, NWT, MS>), dim3(p.blocks), dim3(PW_THREADS), p.lds, s, p.a, p.g);
+    hipLaunchKernelGGL((conv_wide_kernel<TAPS, CPT, XB, KS, NWT, MS, DEEP>), dim3(p.blocks), dim3(PW_THREADS), p.lds, s, p.a, p.g);
     return (int)hipGetLastError();
   }
 }
 
-template <int TAPS, int CPT>
+template <int TAPS, int CPT, bool DEEP>
 inline int launch_wide_tc(const WidePlan& p, hipStream_t s) {
-  if (p.xb == 4 && p.ks == 4 && p.nwt == 1 && p.ms == 1) return launch_wide_t<TAPS, CPT, 4, 4, 1, 1>(p, s);
-  if (p.xb == 4 && p.ks == 2 && p.nwt == 2 && p.ms == 1) return launch_wide_t<TAPS, CPT, 4, 2, 2, 1>(p, s);
-  if (p.xb == 4 && p.ks == 1 && p.nwt == 4 && p.ms == 1) return launch_wide_t<TAPS, CPT, 4, 1, 4, 1>(p, s);
-  if (p.xb == 4 && p.ks == 1 && p.nwt == 1 && p.ms == 4) return launch_wide_t<TAPS, CPT, 4, 1, 1, 4>(p, s);
-  if (p.xb == 2 && p.ks == 2 && p.nwt == 2 && p.ms == 1) return launch_wide_t<TAPS, CPT, 2, 2, 2, 1>(p, s);
-  if (p.xb == 2 && p.ks == 4 && p.nwt == 1 && p.ms == 1) return launch_wide_t<TAPS, CPT, 2, 4, 1, 1>(p, s);
-  if (p.xb == 2 && p.ks == 1 && p.nwt == 1 && p.ms == 4) return launch_wide_t<TAPS, CPT, 2, 1, 1, 4>(p, s);
-  if (p.xb == 2 && p.ks == 1 && p.nwt == 4 && p.ms == 1) return launch_wide_t<TAPS, CPT, 2, 1, 4, 1>(p, s);
+  if (p.xb == 4 && p.ks == 4 && p.nwt == 1 && p.ms == 1) return launch_wide_t<TAPS, CPT, 4, 4, 1, 1, DEEP>(p, s);
+  if (p.xb == 4 && p.ks == 2 && p.nwt == 2 && p.ms == 1) return launch_wide_t<TAPS, CPT, 4, 2, 2, 1, DEEP>(p, s);
+  if (p.xb == 4 && p.ks == 1 && p.nwt == 4 && p.ms == 1) return launch_wide_t<TAPS, CPT, 4, 1, 4, 1, DEEP>(p, s);
+  if (p.xb == 4 && p.ks == 1 && p.nwt == 1 && p.ms == 4) return launch_wide_t<TAPS, CPT, 4, 1, 1, 4, DEEP>(p, s);
+  if (p.xb == 2 && p.ks == 2 && p.nwt == 2 && p.ms == 1) return launch_wide_t<TAPS, CPT, 2, 2, 2, 1, DEEP>(p, s);
+  if (p.xb == 2 && p.ks == 4 && p.nwt == 1 && p.ms == 1) return launch_wide_t<TAPS, CPT, 2, 4, 1, 1, DEEP>(p, s);
+  if (p.xb == 2 && p.ks == 1 && p.nwt == 1 && p.ms == 4) return launch_wide_t<TAPS, CPT, 2, 1, 1, 4, DEEP>(p, s);
+  if (p.xb == 2 && p.ks == 1 && p.nwt == 4 && p.ms == 1) return launch_wide_t<TAPS, CPT, 2, 1, 4, 1, DEEP>(p, s);
   return (int)hipErrorInvalidValue;
 }
 

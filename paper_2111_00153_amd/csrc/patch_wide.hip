@@ -11,8 +11,14 @@ namespace rmsmp {
 #ifndef RMSMP_WIDE_FAMILIES  // (a tuning build may restrict the families it links)
 #define RMSMP_WIDE_FAMILIES(X) X(9, 2) X(9, 4) X(9, 8) X(9, 16) X(1, 2) X(1, 4) X(1, 8) X(1, 16) X(1, 24)
 #endif
+#ifndef RMSMP_WIDE_DEEP_FAMILIES  // channel counts (in K steps) a deep 1x1 layer / GEMM is staged in parts of
+#define RMSMP_WIDE_DEEP_FAMILIES(X) X(16) X(24)
+#endif
 #define RMSMP_WIDE_DECL(TP, CP) int launch_wide_##TP##_##CP(const WidePlan& p, hipStream_t s);
 RMSMP_WIDE_FAMILIES(RMSMP_WIDE_DECL)
+#undef RMSMP_WIDE_DECL
+#define RMSMP_WIDE_DECL(CP) int launch_wide_deep_##CP(const WidePlan& p, hipStream_t s);
+RMSMP_WIDE_DEEP_FAMILIES(RMSMP_WIDE_DECL)
 #undef RMSMP_WIDE_DECL
 
 static uint32_t wide_div_magic(int64_t d) {
@@ -21,19 +27,20 @@ static uint32_t wide_div_magic(int64_t d) {
 
 
 // One candidate split of the four waves; fills the plan when the layer fits it.
-static bool wide_plan_mode(const GemmArgs& a, int xb, int ks, int nwt, int ms, WidePlan* plan) {
+// cc: channels staged at a time (all of them, or a part of a deep 1x1 layer / GEMM).
+static bool wide_plan_mode(const GemmArgs& a, int cc, int xb, int ks, int nwt, int ms, WidePlan* plan) {
   const bool known = (xb == 4 && ((ks == 4 && nwt == 1 && ms == 1) || (ks == 2 && nwt == 2 && ms == 1) ||
                                  (ks == 1 && nwt == 4 && ms == 1) || (ks == 1 && nwt == 1 && ms == 4))) ||
                      (xb == 2 && ((ks == 2 && nwt == 2 && ms == 1) || (ks == 4 && nwt == 1 && ms == 1) ||
                                  (ks == 1 && nwt == 1 && ms == 4) || (ks == 1 && nwt == 4 && ms == 1)));
   if (!known) return false;
-  const int cpt = a.d.C / KSTEP;
+  const int cpt = cc / KSTEP;
   if (cpt % ks != 0 || a.d.KH * a.d.KW * (cpt / ks) < 2) return false;
   const int64_t S = a.d.stride;
   const int64_t row_extra = S * ((int64_t)a.d.W - a.OW);
   const int64_t img_extra = (int64_t)a.d.W * ((int64_t)a.d.H - S * a.OH);
   const int64_t hw = (int64_t)a.OH * a.OW, in_px = (int64_t)a.d.B * a.d.H * a.d.W;
-  const int rs = a.d.C + 16;
+  const int rs = cc + 16;
   const int64_t bn = (int64_t)32 * xb * nwt;
   // widest run of flattened input pixels a tile of bn output pixels touches
   const int64_t rows_crossed = (bn + a.OW - 1) / a.OW + 1, imgs_crossed = (bn + hw - 1) / hw + 1;
@@ -58,6 +65,9 @@ static bool wide_plan_mode(const GemmArgs& a, int xb, int ks, int nwt, int ms, W
   plan->g.row_stride = rs;
   plan->g.patch_rows = (int)span;
   plan->g.gather = gather ? 1 : 0;
+  plan->g.nchunk = a.d.C / cc;
+  plan->g.pix_bytes = a.d.C / 2;
+  plan->cpt = cpt;
   plan->g.magic_hw = wide_div_magic(hw);
   plan->g.magic_ow = wide_div_magic(a.OW);
   plan->lds = lds;
@@ -79,7 +89,7 @@ static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
   if (a0.ep.act_bits != 4) return false;
   GemmArgs a = a0;
   if (!a.conv) {
-    if (a.K % (2 * KSTEP) != 0 || a.K > 1024 || a.N >= ((int64_t)1 << 30)) return false;
+    if (a.K % (2 * KSTEP) != 0 || a.K > 64 * 768 || a.N >= ((int64_t)1 << 30)) return false;
     a.conv = 1;
     a.d = rmsmp_conv_desc{(int32_t)a.N, (int32_t)a.K, 1, 1, 1, 1, 1, 0};
     a.OH = a.OW = 1;
@@ -89,9 +99,22 @@ static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
   // a strided 1x1 layer stages only the pixels it uses (one per output pixel); padding would need
   // out-of-image pixels there
   if (taps == 1 && a.d.stride > 1 && a.d.pad != 0) return false;
-  const int cpt = a.d.C / KSTEP;
-  if (a.d.C % KSTEP != 0 || !wide_cpt_supported(taps, cpt)) return false;
-  if (a.w.nks != taps * cpt) return false;
+  // Channels staged at a time: all of them when the kernel exists for that count; a 1x1 layer of
+  // stride 1 (a GEMM) with more takes them in equal parts, the largest part the kernel exists for.
+  if (a.d.C % KSTEP != 0) return false;
+  int cc = a.d.C;
+  if (!wide_cpt_supported(taps, cc / KSTEP)) {
+    if (!(taps == 1 && a.d.stride == 1)) return false;
+    cc = 0;
+    for (int c : {768, 512})
+      if (a.d.C % c == 0 && a.d.C / c <= 64) {
+        cc = c;
+        break;
+      }
+    if (cc == 0) return false;
+  }
+  const int cpt = cc / KSTEP, nchunk = a.d.C / cc;
+  if (a.w.nks != taps * cpt * nchunk) return false;
   // The flattened input index of tap (0,0) must grow with the output pixel number, also across
   // output rows and images, so that a tile's pixels lie in one contiguous run of the input.
   const int64_t S = a.d.stride;
@@ -113,16 +136,17 @@ static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
   for (const Mode& m : modes) {
     if (m.ms > 1 && n_pairs < m.ms) continue;
     WidePlan p;
-    if (!wide_plan_mode(a, m.xb, m.ks, m.nwt, m.ms, &p)) continue;
+    if (!wide_plan_mode(a, cc, m.xb, m.ks, m.nwt, m.ms, &p)) continue;
     const double wgs = (double)p.g.gx * p.g.gy;
-    const double steps = (double)taps * cpt / m.ks;
+    const double steps = (double)taps * cpt * nchunk / m.ks;
     const double mfmas = steps * 2 * m.xb;
     const double kloop = mfmas * (m.xb == 4 ? 50.0 : 58.0);
-    const double prologue = 1300.0 + (double)p.g.patch_rows * p.g.row_stride / 15.7;
+    // (every further part of the channels is staged like the first, between two barriers)
+    const double prologue = 1300.0 + (double)p.g.patch_rows * p.g.row_stride / 15.7 + (nchunk - 1) * (1500.0 + (double)p.g.patch_rows * p.g.row_stride / 15.7);
     const double exchange = m.ks == 1 ? 0.0 : 400.0 + (double)pw_xch_bytes(m.xb, m.ks) / 45.0;
     const double epilogue = 1800.0 + 670.0 * (2.0 * m.xb / m.ks);
     const double t_wg = prologue + kloop + exchange + epilogue;
-    const int by_lds = (int)((160 * 1024) / p.lds), by_regs = m.xb == 4 ? 2 : 3;
+    const int by_lds = (int)((160 * 1024) / p.lds), by_regs = (m.xb == 4 || nchunk > 1) ? 2 : 3;
     const int k_max = by_lds < by_regs ? by_lds : by_regs;
     const double per_cu = wgs / 256.0;
     // what one more work-group on the same compute unit adds: its MFMAs (the matrix pipe is
@@ -147,7 +171,14 @@ static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
 
 static int launch_wide(const WidePlan& p, hipStream_t s) {
   const int taps = p.a.d.KH * p.a.d.KW;
-  const int cpt = p.a.d.C / KSTEP;
+  const int cpt = p.cpt;
+  if (p.g.nchunk > 1) {
+#define RMSMP_WIDE_CASE(CP) \
+  if (taps == 1 && cpt == CP) return launch_wide_deep_##CP(p, s);
+    RMSMP_WIDE_DEEP_FAMILIES(RMSMP_WIDE_CASE)
+#undef RMSMP_WIDE_CASE
+    return (int)hipErrorInvalidValue;
+  }
 #define RMSMP_WIDE_CASE(TP, CP) \
   if (taps == TP && cpt == CP) return launch_wide_##TP##_##CP(p, s);
   RMSMP_WIDE_FAMILIES(RMSMP_WIDE_CASE)
@@ -161,7 +192,7 @@ int try_launch_wide(const GemmArgs& a, void* stream, bool* applied) {
   *applied = wide_kernel_applies(a, &plan);
   if (*applied && g_forced_split[0] > 0) {
     WidePlan p2;
-    if (wide_plan_mode(plan.a, g_forced_split[0], g_forced_split[1], g_forced_split[2], g_forced_split[3], &p2)) plan = p2;
+    if (wide_plan_mode(plan.a, plan.cpt * KSTEP, g_forced_split[0], g_forced_split[1], g_forced_split[2], g_forced_split[3], &p2)) plan = p2;
   }
   if (!*applied) return 0;
   DispatchRecord& rec = last_dispatch();

@@ -140,6 +140,48 @@ def test_lds_resident_kernel_gemm_every_wave_split(rm, oracle, split, M, K, N):
         p.free()
 
 
+@pytest.mark.parametrize("split", SPLITS)
+@pytest.mark.parametrize("M,K,N", [(200, 3072, 300), (96, 1024, 130), (64, 2304, 257), (130, 4096, 70)])
+def test_lds_resident_kernel_deep_gemm_every_wave_split(rm, oracle, split, M, K, N):
+    """GEMMs deeper than one LDS patch: the channels are staged in equal parts (4 x 768, 2 x 512, 3 x 768,
+    8 x 512) with the accumulators kept across the parts, in every wave split; 4-bit output too."""
+    rng = np.random.default_rng(M + K + N + sum(split))
+    W = si.weights_rowscaled(rng, M, K)
+    scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, 35, 60, 5))
+    xq = si.act_codes_u4(rng, (N, K))
+    z = 3
+    ref = oracle.quantize_rows(W, scheme)
+    acc = oracle.gemm_acc(ref["wint"], xq.astype(np.int32))
+    rs = oracle.rowsum(ref["wint"])
+    acc_c, y, _ = oracle.epilogue(acc, rs, z, ref["rowscale"], 0.05, None, True)
+    p = rm.rmsmp_pack_weights(W, scheme)
+    X = _to_dev(rm.pack_u4(xq))
+    rm.rmsmp_debug_set_wave_split(*split)
+    try:
+        Y = torch.full((M, N), -777, dtype=torch.int32, device=DEV)
+        rm.rmsmp_gemm(p, X, N, rm.make_epilogue(0.05, z, 4, None, False, rm.OUT_INT32), Y)
+        assert rm.rmsmp_debug_last_dispatch()[0] == "lds_resident"
+        Yf = torch.full((M, N), np.nan, dtype=torch.float32, device=DEV)
+        rm.rmsmp_gemm(p, X, N, rm.make_epilogue(0.05, z, 4, None, True, rm.OUT_FP32), Yf)
+        pos = y[y > 0]
+        inv = np.float32(15.0 / max(float(np.percentile(pos, 99.0)) if pos.size else 1.0, 1e-6))
+        _, _, q = oracle.epilogue(acc, rs, z, ref["rowscale"], 0.05, None, True, inv)
+        Yq = torch.full((N, M // 2), 0xEE, dtype=torch.uint8, device=DEV)
+        rm.rmsmp_gemm(p, X, N, rm.make_epilogue(0.05, z, 4, None, True, rm.OUT_U4, inv), Yq)
+        torch.cuda.synchronize()
+        assert np.array_equal(Y.cpu().numpy(), acc_c)
+        assert np.all(np.abs(Yf.cpu().numpy() - y) <= 1e-5 * np.abs(y))
+        assert np.array_equal(_grouped_codes(rm, Yq.cpu().numpy(), p.perm), q)
+    finally:
+        rm.rmsmp_debug_set_wave_split(0, 0, 0, 0)
+        p.free()
+
+
+def test_lds_resident_kernel_deep_1x1_layer(rm, oracle):
+    """A 1x1 layer of stride 1 with 1024 input channels (a ResNet-50 bottleneck's shape): two parts of 512."""
+    _check_conv(rm, oracle, (2, 1024, 7, 9, 1, 1, 1, 0), 96, (35, 60, 5), 4, 5, True, True, 41, "lds_resident")
+
+
 @pytest.mark.parametrize("geom", [(2, 3, 32, 32, 7, 7, 2, 3), (1, 3, 70, 44, 7, 7, 2, 3), (3, 3, 36, 40, 3, 3, 2, 1),
                                   (2, 3, 35, 36, 5, 5, 2, 1), (1, 3, 18, 8, 5, 5, 2, 3), (5, 3, 16, 16, 7, 7, 2, 3)])
 @pytest.mark.parametrize("M,ratio", [(64, (0, 0, 100)), (40, (35, 60, 5)), (160, (35, 60, 5))])
