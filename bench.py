@@ -22,7 +22,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the timed kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a
 # 256 MiB device copy (profiles/conv_wide_kernel_configs1.md); a counter reading cannot be taken from
 # inside this script, so the last measured value is carried here.
-MEASURED_TRAFFIC_BYTES = 5114236
+MEASURED_TRAFFIC_BYTES = 5090639
 
 
 def make_conv_workload(cfg_id=1):
@@ -121,7 +121,7 @@ def main():
     kern_ms = gpu_ms / args.steps
     achieved = ops / (kern_ms * 1e-3) / 1e12
     kernel, split = rm.rmsmp_debug_last_dispatch()
-    kernel_name = ("rmsmp::conv_wide_kernel<9, 8, %d, %d, %d, %d>" % split) if kernel == "lds_resident" else kernel
+    kernel_name = ("rmsmp::conv_wide_kernel<9, 8, %d, %d, %d, %d, false>" % split) if kernel == "lds_resident" else kernel
 
     if base is not None:
         # spot check of the timed configuration against the oracle (first images)
