@@ -61,7 +61,7 @@ struct WideGeom {
 };
 
 // bytes of the partial-sum exchange buffer: every wave parks the blocks it does not finish
-constexpr int pw_xch_bytes(int xb, int ks) { return ks == 1 ? 0 : 4 * (2 * xb - 2 * xb / ks) * 16 * LANES * 4; }
+constexpr int pw_xch_bytes(int xb, int ks, int waves = 4) { return ks == 1 ? 0 : waves * (2 * xb - 2 * xb / ks) * 16 * LANES * 4; }
 
 __device__ __forceinline__ int wide_fast_div(int n, uint32_t magic) {
   return magic ? (int)__umulhi((uint32_t)n, magic) : n;
@@ -152,7 +152,11 @@ template <int TAPS, int CPT, int XB, int KS, int NWT, int MS, bool DEEP, int KIN
 __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, const WideGeom& g, int bx, int pair,
                                           bool pair_live, WidePatchLoads& pl) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
-  static_assert(KS * NWT * MS == 4, "four waves");
+  // waves per work-group: four in every split in use (eight, two per SIMD, measured no faster on
+  // the benchmarked layer and is not instantiated)
+  constexpr int NW = KS * NWT * MS;
+  static_assert(NW == 4 || NW == 8, "four or eight waves");
+  constexpr int NT = LANES * NW;
   static_assert(XB == 2 || XB == 4, "32-pixel blocks per wave");
   constexpr int PW_XB = XB;
   constexpr int PW_WAVE_PX = 32 * XB;
@@ -292,16 +296,16 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
   auto stage_patch = [&](const int t0) {
 #pragma unroll
     for (int u = 0; u < PW_PATCH_UNROLL; ++u) {
-      const int idx = u * PW_THREADS + t0;
+      const int idx = u * NT + t0;
       if (idx < total) put_piece(idx, pw[u]);
     }
 #pragma unroll 1
-    for (int base = PW_THREADS * PW_PATCH_UNROLL; base < total; base += PW_THREADS * PW_PATCH_UNROLL) {
+    for (int base = NT * PW_PATCH_UNROLL; base < total; base += NT * PW_PATCH_UNROLL) {
 #pragma unroll
-      for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece<PIECES>(pl, base + u * PW_THREADS + t0);
+      for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece<PIECES>(pl, base + u * NT + t0);
 #pragma unroll
       for (int u = 0; u < PW_PATCH_UNROLL; ++u) {
-        const int idx = base + u * PW_THREADS + t0;
+        const int idx = base + u * NT + t0;
         if (idx < total) put_piece(idx, pw[u]);
       }
     }
@@ -345,7 +349,7 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
       if constexpr (!PREFETCH) {
         pl.src0 += C / 2;
 #pragma unroll
-        for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece<PIECES>(pl, u * PW_THREADS + t0);
+        for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece<PIECES>(pl, u * NT + t0);
       }
       stage_patch(t0);
       __syncthreads();
@@ -355,7 +359,7 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
       int t0 = tid;
       asm volatile("" : "+v"(t0));
 #pragma unroll
-      for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece<PIECES>(pl, u * PW_THREADS + t0);
+      for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece<PIECES>(pl, u * NT + t0);
     }
     int cur[PW_XB];
     v4i b[PW_XB];
@@ -439,54 +443,62 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
     __syncthreads();  // the exchange buffer overlays the patch: every wave is done reading it
     const int grp = wave % (NWT * MS);  // which 64 x 128 block of the work-group
     int* const blk = (int*)xch + grp * (KS * (NBLK - OWN) * 16 * LANES);
-    auto exchange = [&](auto kq_tag) {
+    // Which accumulators are given and which are kept depends on kq, and registers cannot be
+    // indexed at run time: the two selections are KS copies of the code under a wave-uniform
+    // branch.  The barrier and the reads of the others' blocks (addresses computed from kq) are
+    // common code.  (With the barrier and the reads inside the per-role copies, hipcc 7.2 merged
+    // the copies' tails and, in a variant with eight waves, left one role's first read address
+    // unset: keep the roles free of barriers.)
+    auto give = [&](auto kq_tag) {
       constexpr int KQ = decltype(kq_tag)::value;
-      {
-        int* dst = blk + KQ * ((NBLK - OWN) * 16 * LANES);
-        int gi = 0;
+      int* dst = blk + KQ * ((NBLK - OWN) * 16 * LANES);
+      int gi = 0;
 #pragma unroll
-        for (int q = 0; q < NBLK; ++q) {
-          if (q / OWN == KQ) continue;
+      for (int q = 0; q < NBLK; ++q) {
+        if (q / OWN == KQ) continue;
 #pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            v4i gq;
+        for (int c = 0; c < 4; ++c) {
+          v4i gq;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) gq[e] = acc[q / PW_XB][q % PW_XB][4 * c + e];
-            *(v4i*)(dst + gi * (16 * LANES) + c * (4 * LANES) + lane * 4) = gq;
-          }
-          ++gi;
+          for (int e = 0; e < 4; ++e) gq[e] = acc[q / PW_XB][q % PW_XB][4 * c + e];
+          *(v4i*)(dst + gi * (16 * LANES) + c * (4 * LANES) + lane * 4) = gq;
         }
+        ++gi;
       }
-      __syncthreads();
-      RMSMP_PHASE(4);
 #pragma unroll
       for (int o = 0; o < OWN; ++o) {
         constexpr int q0 = KQ * OWN;
-        const int q = q0 + o;
-        mine[o] = acc[q / PW_XB][q % PW_XB];
-#pragma unroll
-        for (int gk = 0; gk < KS; ++gk) {
-          if (gk == KQ) continue;
-          // where giver gk put block q: its given blocks are all but its own, in order
-          const int gi = q < gk * OWN ? q : q - OWN;
-          const int* src = blk + gk * ((NBLK - OWN) * 16 * LANES) + gi * (16 * LANES);
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const v4i got = *(const v4i*)(src + c * (4 * LANES) + lane * 4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) mine[o][4 * c + e] += got[e];
-          }
-        }
+        mine[o] = acc[(q0 + o) / PW_XB][(q0 + o) % PW_XB];
       }
     };
     if (kq == 0)
-      exchange(std::integral_constant<int, 0>{});
+      give(std::integral_constant<int, 0>{});
     else if (kq == 1)
-      exchange(std::integral_constant<int, 1>{});
+      give(std::integral_constant<int, 1>{});
     else if (KS == 4 && kq == 2)
-      exchange(std::integral_constant<int, KS == 4 ? 2 : 0>{});
+      give(std::integral_constant<int, KS == 4 ? 2 : 0>{});
     else if (KS == 4)
-      exchange(std::integral_constant<int, KS == 4 ? 3 : 0>{});
+      give(std::integral_constant<int, KS == 4 ? 3 : 0>{});
+    __syncthreads();
+    RMSMP_PHASE(4);
+#pragma unroll
+    for (int o = 0; o < OWN; ++o) {
+      const int q = kq * OWN + o;
+#pragma unroll
+      for (int d = 1; d < KS; ++d) {
+        // giver gk (every wave of the group but this one) put block q after the blocks before it
+        // that are not its own: at position q if q comes before its own blocks, else OWN earlier
+        const int gk = (kq + d) % KS;
+        const int gi = q < gk * OWN ? q : q - OWN;
+        const int* src = blk + gk * ((NBLK - OWN) * 16 * LANES) + gi * (16 * LANES);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const v4i got = *(const v4i*)(src + c * (4 * LANES) + lane * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) mine[o][4 * c + e] += got[e];
+        }
+      }
+    }
   }
   RMSMP_PHASE(5);
 
@@ -597,7 +609,7 @@ __device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGe
     pl.H = a.d.H, pl.W = a.d.W, pl.S = a.d.stride, pl.magic_hw = g.magic_hw, pl.magic_ow = g.magic_ow;
     if (g.gather) pl.f_lo = 0;
 #pragma unroll
-    for (int u = 0; u < PW_PATCH_UNROLL; ++u) pl.pw[u] = wide_load_piece<CPT>(pl, u * PW_THREADS + (int)threadIdx.x);
+    for (int u = 0; u < PW_PATCH_UNROLL; ++u) pl.pw[u] = wide_load_piece<CPT>(pl, u * (LANES * KS * NWT * MS) + (int)threadIdx.x);
   }
   EpArgs ea = pin_epilogue_args(a);
   ea.stamps = PHASE_LDS_BYTES != 0;
@@ -624,7 +636,7 @@ __device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGe
 }
 
 template <int TAPS, int CPT, int XB, int KS, int NWT, int MS, bool DEEP>
-__global__ __launch_bounds__(PW_THREADS, 2) void conv_wide_kernel(GemmArgs a, WideGeom g) {
+__global__ __launch_bounds__(LANES * KS * NWT * MS, KS * NWT * MS == 8 ? 1 : 2) void conv_wide_kernel(GemmArgs a, WideGeom g) {
   wide_kernel_impl<TAPS, CPT, XB, KS, NWT, MS, DEEP>(a, g);
 }
 
@@ -654,7 +666,7 @@ inline int launch_wide_t(const WidePlan& p, hipStream_t s) {
       if (e != hipSuccess) return (int)e;
       allowed[dev] = true;
     }
-    hipLaunchKernelGGL((conv_wide_kernel<TAPS, CPT, XB, KS, NWT, MS, DEEP>), dim3(p.blocks), dim3(PW_THREADS), p.lds, s, p.a, p.g);
+    hipLaunchKernelGGL((conv_wide_kernel<TAPS, CPT, XB, KS, NWT, MS, DEEP>), dim3(p.blocks), dim3(LANES * KS * NWT * MS), p.lds, s, p.a, p.g);
     return (int)hipGetLastError();
   }
 }

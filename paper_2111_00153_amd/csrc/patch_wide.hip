@@ -52,7 +52,7 @@ static bool wide_plan_mode(const GemmArgs& a, int cc, int xb, int ks, int nwt, i
   if (in_px + span >= ((int64_t)1 << 31) / rs) return false;
   // 24-bit LDS address arithmetic
   const size_t need = (size_t)(span + 1) * rs;  // patch + zero-point row
-  const size_t xch = (size_t)pw_xch_bytes(xb, ks);
+  const size_t xch = (size_t)pw_xch_bytes(xb, ks, ks * nwt * ms);
   const size_t lds = PHASE_LDS_BYTES + (size_t)ms * PW_META_BYTES + (need > xch ? need : xch);
   if (lds > 160 * 1024) return false;
   const int n_pairs = (a.w.n_tiles + 1) / 2;
@@ -143,7 +143,7 @@ static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
     const double kloop = mfmas * (m.xb == 4 ? 50.0 : 58.0);
     // (every further part of the channels is staged like the first, between two barriers)
     const double prologue = 1300.0 + (double)p.g.patch_rows * p.g.row_stride / 15.7 + (nchunk - 1) * (1500.0 + (double)p.g.patch_rows * p.g.row_stride / 15.7);
-    const double exchange = m.ks == 1 ? 0.0 : 400.0 + (double)pw_xch_bytes(m.xb, m.ks) / 45.0;
+    const double exchange = m.ks == 1 ? 0.0 : 400.0 + (double)pw_xch_bytes(m.xb, m.ks, m.ks * m.nwt * m.ms) / 45.0;
     const double epilogue = 1800.0 + 670.0 * (2.0 * m.xb / m.ks);
     const double t_wg = prologue + kloop + exchange + epilogue;
     const int by_lds = (int)((160 * 1024) / p.lds), by_regs = (m.xb == 4 || nchunk > 1) ? 2 : 3;
