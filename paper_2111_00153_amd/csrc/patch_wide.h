@@ -361,12 +361,12 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
 #pragma unroll
       for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece<PIECES>(pl, u * NT + t0);
     }
-    int cur[PW_XB];
+    const uint8_t* cur[PW_XB];  // LDS address of the lane's B fragment at the current tap
     v4i b[PW_XB];
 #pragma unroll
     for (int j = 0; j < PW_XB; ++j) {
-      cur[j] = tap_addr(0, j);
-      b[j] = *(const v4i*)(zrow + cur[j]);
+      cur[j] = zrow + tap_addr(0, j);
+      b[j] = *(const v4i*)cur[j];
     }
     // Software pipeline, one K step = four sub-blocks, one per 32-pixel block j: the two MFMAs of
     // the block, then word j of both weight fragments of the NEXT step is decoded, then the
@@ -401,8 +401,8 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
             nav0[ci] = decode_word<KIND0, ci>(ring0[slot], T0);
             nav1[ci] = decode_word<KIND1, ci>(ring1[slot], T1);
           });
-          if constexpr (new_tap) cur[j] = tap_addr(t, j);
-          b[j] = *(const v4i*)(zrow + cur[j] + boff);
+          if constexpr (new_tap) cur[j] = zrow + tap_addr(t, j);
+          b[j] = *(const v4i*)(cur[j] + boff);
           if constexpr (j == PW_XB - 1) {
             // the ring slot is used up: refill it R steps further on
             int gs = ch * NSTEP + it * BODY + (u + 1 + R);
