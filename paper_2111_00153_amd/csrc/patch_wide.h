@@ -389,8 +389,11 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
         constexpr bool new_tap = (u + 1) % SPT == 0;
         constexpr int boff = ((u + 1) % SPT) * KS * KSTEP;
         constexpr int NVH = ((NV0 + NV1) * (4 / PW_XB) + (new_tap ? 3 : 0) + 1) / 2;  // vector instructions per MFMA slot
-        // tap of the next step
+        // tap of the next step; with a filter row per iteration its row is the iteration number and
+        // its column a constant, so that the tap's offset needs no division
         const int t = (it + (wraps ? 1 : 0)) * BT + (wraps ? 0 : (u + 1) / SPT);
+        constexpr int kw_next = wraps ? 0 : (u + 1) / SPT;
+        const int tapoff_next = BT == 3 ? (it + (wraps ? 1 : 0)) * tap_row_bytes + kw_next * row_stride : 0;
         v4i nav0, nav1;
         static_for<0, PW_XB>([&](auto j_tag) {
           constexpr int j = decltype(j_tag)::value;
@@ -401,7 +404,12 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
             nav0[ci] = decode_word<KIND0, ci>(ring0[slot], T0);
             nav1[ci] = decode_word<KIND1, ci>(ring1[slot], T1);
           });
-          if constexpr (new_tap) cur[j] = zrow + tap_addr(t, j);
+          if constexpr (new_tap) {
+            if constexpr (BT == 3)
+              cur[j] = zrow + (__builtin_amdgcn_sbfe((int)vm[j], t, 1) & (dlt[j] + tapoff_next));
+            else
+              cur[j] = zrow + tap_addr(t, j);
+          }
           b[j] = *(const v4i*)(cur[j] + boff);
           if constexpr (j == PW_XB - 1) {
             // the ring slot is used up: refill it R steps further on
