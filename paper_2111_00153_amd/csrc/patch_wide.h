@@ -198,12 +198,14 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
   const bool two = mt1 > mt0;
 
   // flattened input index of tap (0,0) for output pixel n (may be negative / out of image)
+  // (pixel counts are below 2^23, checked by the host: the products are 24-bit multiplications,
+  // which run at full rate where a 32-bit one takes four times as long)
   auto base_index = [&](int n, int& oh, int& ow) -> int {
     const int b = wide_fast_div(n, g.magic_hw);
-    const int rem = n - b * hw_out;
+    const int rem = n - __mul24(b, hw_out);
     oh = wide_fast_div(rem, g.magic_ow);
-    ow = rem - oh * a.OW;
-    return (b * H + (oh * S - pad)) * W + (ow * S - pad);
+    ow = rem - __mul24(oh, a.OW);
+    return __mul24(__mul24(b, H) + (__mul24(oh, S) - pad), W) + (__mul24(ow, S) - pad);
   };
   const int f_lo = pl.f_lo;
 
@@ -274,7 +276,7 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
 #pragma unroll
     for (int kh = 0; kh < KH; ++kh) m |= (kh >= kh_lo && kh <= kh_hi) ? wbits << (KW * kh) : 0u;
     vm[j] = n_ok ? m : 0u;
-    dlt[j] = (C + 16) + (g.gather ? (n_ok ? n - n0 : 0) : f0 - f_lo) * row_stride + lane_off;
+    dlt[j] = (C + 16) + __mul24(g.gather ? (n_ok ? n - n0 : 0) : f0 - f_lo, row_stride) + lane_off;
   }
   const int tap_row_bytes = W * row_stride;
   // LDS address (from zrow) of the lane's B fragments at tap t (wave-uniform; may be TAPS: nothing valid)

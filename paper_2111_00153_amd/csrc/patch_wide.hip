@@ -50,6 +50,8 @@ static bool wide_plan_mode(const GemmArgs& a, int cc, int xb, int ks, int nwt, i
   // 32-bit pixel arithmetic and exact one-multiply division in the kernel
   if ((a.N + bn) * hw >= ((int64_t)1 << 32) || in_px * (a.d.C / 2) >= ((int64_t)1 << 31) || in_px * (a.d.C / 2) < 16) return false;
   if (in_px + span >= ((int64_t)1 << 31) / rs) return false;
+  // 24-bit multiplications in the kernel's pixel index arithmetic
+  if (in_px + span >= ((int64_t)1 << 23) || a.N + bn >= ((int64_t)1 << 23) || hw >= ((int64_t)1 << 23)) return false;
   // 24-bit LDS address arithmetic
   const size_t need = (size_t)(span + 1) * rs;  // patch + zero-point row
   const size_t xch = (size_t)pw_xch_bytes(xb, ks, ks * nwt * ms);
