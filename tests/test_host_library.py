@@ -167,3 +167,15 @@ def test_nibble_helpers(rm):
     b = rm.pack_u4(c)
     assert b.shape == (2, 8) and b[0, 0] == (0 | (1 << 4))
     assert np.array_equal(rm.unpack_u4(b), c)
+
+
+def test_build_entry_point_works_without_the_library():
+    """build() must be able to run in a tree that has no librmsmp.so yet: it loads the build script by
+    path, and that script imports nothing from the package (whose import needs the library)."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    entry = open(os.path.join(root, "__graft_entry__.py")).read()
+    build_fn = entry[entry.index("def build"):entry.index("def smoke")]
+    assert "spec_from_file_location" in build_fn
+    assert build_fn.index("build_library") < build_fn.index("import paper_2111_00153_amd")
+    script = open(os.path.join(root, "paper_2111_00153_amd", "build.py")).read()
+    assert not re.search(r"^\s*(from \.|from paper_2111_00153_amd|import paper_2111_00153_amd)", script, re.M)
