@@ -42,7 +42,11 @@
 namespace rmsmp {
 
 constexpr int PW_THREADS = 256;
-constexpr int PW_PATCH_UNROLL = 6;  // 16-byte patch pieces in flight per thread
+constexpr int PW_PATCH_UNROLL = 6;  // 16-byte patch pieces in flight per thread, at most
+// The patches of the 3x3 layers at hand are just under five pieces per thread (128 pixels plus halo
+// x 8 pieces, 512 + halo x 2, ...), those of the 1x1 layers / GEMMs exactly six (64 x 24): a batch
+// of five is one read, one decode and four registers less for the former.
+constexpr int pw_batch(int taps) { return taps == 9 ? 5 : PW_PATCH_UNROLL; }
 // Row metadata of a tile pair in LDS, field by field [field][64 rows]: rowscale bits, rowsum, original
 // row, grouped position, and two values formed once per work-group for the lean 4-bit epilogue: the
 // row's multiplier rowscale * activation scale (* 1/16 for shift-decoded tiles) and zero point * rowsum
@@ -236,6 +240,7 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
     *(v4i*)(dst + 16) = decode_act_u4(make_uint2(w.z, w.w));
   };
   uint4 (&pw)[PW_PATCH_UNROLL] = pl.pw;
+  constexpr int PU = pw_batch(TAPS);
 #pragma unroll
   for (int u = 0; u < R; ++u) {
     ring0[u] = wide_load<KIND0>(wb0, wl0, u * KS * step0);
@@ -297,16 +302,16 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
   // ---- 3. the patch goes to LDS, batch by batch (the first batch is already in registers)
   auto stage_patch = [&](const int t0) {
 #pragma unroll
-    for (int u = 0; u < PW_PATCH_UNROLL; ++u) {
+    for (int u = 0; u < PU; ++u) {
       const int idx = u * NT + t0;
       if (idx < total) put_piece(idx, pw[u]);
     }
 #pragma unroll 1
-    for (int base = NT * PW_PATCH_UNROLL; base < total; base += NT * PW_PATCH_UNROLL) {
+    for (int base = NT * PU; base < total; base += NT * PU) {
 #pragma unroll
-      for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece<PIECES>(pl, base + u * NT + t0);
+      for (int u = 0; u < PU; ++u) pw[u] = wide_load_piece<PIECES>(pl, base + u * NT + t0);
 #pragma unroll
-      for (int u = 0; u < PW_PATCH_UNROLL; ++u) {
+      for (int u = 0; u < PU; ++u) {
         const int idx = base + u * NT + t0;
         if (idx < total) put_piece(idx, pw[u]);
       }
@@ -351,7 +356,7 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
       if constexpr (!PREFETCH) {
         pl.src0 += C / 2;
 #pragma unroll
-        for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece<PIECES>(pl, u * NT + t0);
+        for (int u = 0; u < PU; ++u) pw[u] = wide_load_piece<PIECES>(pl, u * NT + t0);
       }
       stage_patch(t0);
       __syncthreads();
@@ -361,7 +366,7 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
       int t0 = tid;
       asm volatile("" : "+v"(t0));
 #pragma unroll
-      for (int u = 0; u < PW_PATCH_UNROLL; ++u) pw[u] = wide_load_piece<PIECES>(pl, u * NT + t0);
+      for (int u = 0; u < PU; ++u) pw[u] = wide_load_piece<PIECES>(pl, u * NT + t0);
     }
     const uint8_t* cur[PW_XB];  // LDS address of the lane's B fragment at the current tap
     v4i b[PW_XB];
@@ -619,7 +624,7 @@ __device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGe
     pl.H = a.d.H, pl.W = a.d.W, pl.S = a.d.stride, pl.magic_hw = g.magic_hw, pl.magic_ow = g.magic_ow;
     if (g.gather) pl.f_lo = 0;
 #pragma unroll
-    for (int u = 0; u < PW_PATCH_UNROLL; ++u) pl.pw[u] = wide_load_piece<CPT>(pl, u * (LANES * KS * NWT * MS) + (int)threadIdx.x);
+    for (int u = 0; u < pw_batch(TAPS); ++u) pl.pw[u] = wide_load_piece<CPT>(pl, u * (LANES * KS * NWT * MS) + (int)threadIdx.x);
   }
   EpArgs ea = pin_epilogue_args(a);
   ea.stamps = PHASE_LDS_BYTES != 0;
