@@ -281,7 +281,8 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
 #pragma unroll
     for (int kh = 0; kh < KH; ++kh) m |= (kh >= kh_lo && kh <= kh_hi) ? wbits << (KW * kh) : 0u;
     vm[j] = n_ok ? m : 0u;
-    dlt[j] = (C + 16) + __mul24(g.gather ? (n_ok ? n - n0 : 0) : f0 - f_lo, row_stride) + lane_off;
+    // (only 1x1 layers are ever gathered: the 3x3 kernels carry none of that code)
+    dlt[j] = (C + 16) + __mul24((TAPS == 1 && g.gather) ? (n_ok ? n - n0 : 0) : f0 - f_lo, row_stride) + lane_off;
   }
   const int tap_row_bytes = W * row_stride;
   // LDS address (from zrow) of the lane's B fragments at tap t (wave-uniform; may be TAPS: nothing valid)
@@ -620,9 +621,9 @@ __device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGe
     pl.src0 = (uint32_t)f_lo * (uint32_t)g.pix_bytes;
     pl.chunked = DEEP, pl.pix_bytes = g.pix_bytes;
     pl.x_last = x_bytes - 16u;
-    pl.gather = g.gather, pl.n0 = n0, pl.n_last = (int)a.N - 1, pl.hw_out = hw_out, pl.OW = a.OW;
+    pl.gather = TAPS == 1 ? g.gather : 0, pl.n0 = n0, pl.n_last = (int)a.N - 1, pl.hw_out = hw_out, pl.OW = a.OW;
     pl.H = a.d.H, pl.W = a.d.W, pl.S = a.d.stride, pl.magic_hw = g.magic_hw, pl.magic_ow = g.magic_ow;
-    if (g.gather) pl.f_lo = 0;
+    if (TAPS == 1 && g.gather) pl.f_lo = 0;
 #pragma unroll
     for (int u = 0; u < pw_batch(TAPS); ++u) pl.pw[u] = wide_load_piece<CPT>(pl, u * (LANES * KS * NWT * MS) + (int)threadIdx.x);
   }
