@@ -22,7 +22,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the timed kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a
 # 256 MiB device copy (profiles/conv_wide_kernel_configs1.md); a counter reading cannot be taken from
 # inside this script, so the last measured value is carried here.
-MEASURED_TRAFFIC_BYTES = 4871522
+MEASURED_TRAFFIC_BYTES = 4861294
 
 
 def make_conv_workload(cfg_id=1):
