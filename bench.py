@@ -1,14 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the RMSMP hot path on one MI355X.
 
-One step = one pass of the whole hot path over one batch: a single rmsmp_conv2d call on the
-ResNet-18-shaped 3x3 layer (batch 32, 256->256 channels, 14x14, stride 1, pad 1; GEMM
-M=256, K=2304, N=6272) with weight rows Fixed4:PoT4:Fixed8 = 60:35:5, unsigned 4-bit
-activations resident in HBM, fused ReLU + 4-bit requantization.  Prints one JSON line.
+One step = one pass of the whole hot path over one batch of configs[3]: the 20 convolutions of
+ResNet-18 at batch 64 and 224x224 (Section 4.2 / Table 6's workload, 232.1 GOP), each one
+rmsmp_conv2d call -- conv1 with Fixed-8 rows and 8-bit activations, the others with weight rows
+Fixed4:PoT4:Fixed8 = 60:35:5 and unsigned 4-bit activations resident in HBM, fused ReLU + 4-bit
+requantization -- launched back to back on one stream.  Prints one JSON line.
+
+Besides the contract fields the line carries: per-layer times, the time share of every kernel
+family, the other configurations (configs[1], configs[2], configs[4] with cold weights), the
+measured MFMA-only and stream-copy rates of this machine, and the CPU oracle's rate.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -19,53 +25,212 @@ sys.path.insert(0, ROOT)
 
 INT8_MFMA_PEAK_TOPS = 5000.0  # MI355X dense int8, published
 HBM_PEAK_GBS = 8000.0
-# HBM-side bytes per launch of the timed kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a
-# 256 MiB device copy (profiles/conv_wide_kernel_configs1.md); a counter reading cannot be taken from
-# inside this script, so the last measured value is carried here.
-MEASURED_TRAFFIC_BYTES = 4861294
+BATCH = 64
 
 
-def make_conv_workload(cfg_id=1):
-    import paper_2111_00153_amd as rm
-    import synth_inputs as si
-    c = si.CONFIGS[cfg_id]
-    rng = si.rng_for(cfg_id)
-    M, C, KH, KW = c["M"], c["C"], c["KH"], c["KW"]
-    K = C * KH * KW
-    W = si.weights_rowscaled(rng, M, K)
-    counts = rm.rmsmp_ratio_counts(M, *c["ratio"])
-    scheme = si.scheme_permutation(rng, counts)
-    x = si.act_codes_u4(rng, (c["B"], c["H"], c["W"], C))
-    return dict(cfg=c, W=W, scheme=scheme, x=x, counts=counts, K=K)
+def _conv_out(h, k, s, p):
+    return (h + 2 * p - k) // s + 1
 
 
-def cpu_baseline(wl, repeats=3):
-    """The oracle, as it stands, on the whole batch of the same workload, `repeats` times over
-    (about 20 core-seconds on 16 host threads)."""
-    import oracle
-    c = wl["cfg"]
-    ref = oracle.quantize_rows(wl["W"], wl["scheme"])
-    d = oracle.conv_desc(c["B"], c["C"], c["H"], c["W"], c["KH"], c["KW"], c["stride"], c["pad"])
-    x = wl["x"].astype(np.int32)
-    wint = ref["wint"].reshape(c["M"], c["C"], c["KH"], c["KW"])
+def make_stack(rm, si, torch, dev, batch, inv_scales=None):
+    """Synthetic ResNet-18 conv stack: packed weights, resident inputs, output buffers, launchers."""
+    layers = []
+    for idx, (name, C, M, k, s, pad, H) in enumerate(si.RESNET18_CONVS):
+        rng = si.rng_for(3, idx)
+        K = C * k * k
+        W = si.weights_rowscaled(rng, M, K)
+        if idx == 0:  # first layer: Fixed-8 rows, signed 8-bit image (Section 4: first and last layers 8-bit)
+            scheme = np.full(M, 2, np.uint8)
+            x, s_x = si.symmetric_i8_from_float(rng.standard_normal((batch, H, H, C)))
+            bits, xdev = 8, x
+        else:
+            scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, 35, 60, 5))
+            x, s_x, bits = si.act_codes_u4(rng, (batch, H, H, C)), 0.05, 4
+            xdev = rm.pack_u4(x)
+        OH = _conv_out(H, k, s, pad)
+        N = batch * OH * OH
+        p = rm.rmsmp_pack_weights(W, scheme, taps=k * k)
+        d = rm.ConvDesc(batch, C, H, H, k, k, s, pad)
+        X = torch.from_numpy(xdev).to(dev)
+        Y = torch.empty((N, M // 2), dtype=torch.uint8, device=dev)
+        inv = np.float32(2.0 if inv_scales is None else inv_scales[idx])
+        ep = rm.make_epilogue(s_x, 0, bits, None, True, rm.OUT_U4, inv)
+        wsb = rm.rmsmp_conv2d_workspace_size(p, d, bits)
+        ws = torch.empty(wsb, dtype=torch.uint8, device=dev) if wsb else None
+        layers.append(dict(idx=idx, name=name, C=C, M=M, k=k, s=s, pad=pad, H=H, OH=OH, N=N, K=K, W=W, scheme=scheme,
+                           x=x, s_x=s_x, bits=bits, p=p, d=d, X=X, Y=Y, ep=ep, inv=inv, ws=ws, ops=2.0 * M * K * N,
+                           launch=rm.conv2d_launcher(p, X, d, ep, Y, ws)))
+    return layers
+
+
+def kernel_of(rm, layer):
+    layer["launch"]()
+    kernel, split = rm.rmsmp_debug_last_dispatch()
+    taps, cpt = layer["k"] * layer["k"], layer["C"] // 32
+    if kernel == "lds_resident":
+        return "rmsmp::conv_wide_kernel<%d, %d, %d, %d, %d, %d, false>" % ((taps, cpt) + split)
+    if kernel == "first_layer":
+        return "rmsmp::conv_first_kernel"
+    return kernel
+
+
+def oracle_reference(oracle, layer, images):
+    """Oracle accumulators -> fp32 output of the given images of one layer (weights quantized by the oracle)."""
+    ref = oracle.quantize_rows(layer["W"], layer["scheme"], want_levels=False)
+    k, C, M = layer["k"], layer["C"], layer["M"]
+    d = oracle.conv_desc(len(images), C, layer["H"], layer["H"], k, k, layer["s"], layer["pad"])
+    acc = oracle.conv_acc(ref["wint"].reshape(M, C, k, k), layer["x"][images].astype(np.int32), d, 0)
     rs = oracle.rowsum(ref["wint"])
+    return ref, acc, rs
+
+
+def cpu_baseline(oracle, si, sample_batch=8):
+    """The oracle as it stands on a bounded sample of the same workload: all 20 layers on
+    `sample_batch` images (all host threads), and the deepest 3x3 layer on one image with one thread."""
+    macs = 0
     t0 = time.perf_counter()
-    for _ in range(repeats):
-        acc = oracle.conv_acc(wint, x, d, 0)
-        _, y, _ = oracle.epilogue(acc, rs, 0, ref["rowscale"], c["s_x"], None, True)
+    for idx, (name, C, M, k, s, pad, H) in enumerate(si.RESNET18_CONVS):
+        rng = si.rng_for(3, idx)
+        W = si.weights_rowscaled(rng, M, C * k * k)
+        scheme = np.full(M, 2, np.uint8) if idx == 0 else si.scheme_permutation(rng, oracle.ratio_counts(M, 35, 60, 5))
+        ref = oracle.quantize_rows(W, scheme, want_levels=False)
+        x = (si.act_codes_i8(rng, (sample_batch, H, H, C)) if idx == 0 else si.act_codes_u4(rng, (sample_batch, H, H, C)))
+        d = oracle.conv_desc(sample_batch, C, H, H, k, k, s, pad)
+        acc = oracle.conv_acc(ref["wint"].reshape(M, C, k, k), x.astype(np.int32), d, 0)
+        oracle.epilogue(acc, oracle.rowsum(ref["wint"]), 0, ref["rowscale"], 0.05, None, True, np.float32(2.0))
+        macs += M * C * k * k * acc.shape[1]
     t1 = time.perf_counter()
-    ops = 2.0 * c["M"] * wl["K"] * acc.shape[1] * repeats
-    return dict(value=ops / (t1 - t0) / 1e12, unit="TOPS", cores=oracle.num_threads(), kind="oracle",
-                sample="all %d images of the same layer, %d passes (%.2f s wall on %d threads)"
-                       % (c["B"], repeats, t1 - t0, oracle.num_threads())), ref, y
+    threads = oracle.num_threads()
+    # one thread, one layer (layer3.1.conv1, 115.6 MMAC per image)
+    name, C, M, k, s, pad, H = si.RESNET18_CONVS[13]
+    rng = si.rng_for(3, 13)
+    W = si.weights_rowscaled(rng, M, C * k * k)
+    ref = oracle.quantize_rows(W, si.scheme_permutation(rng, oracle.ratio_counts(M, 35, 60, 5)), want_levels=False)
+    x = si.act_codes_u4(rng, (1, H, H, C))
+    d = oracle.conv_desc(1, C, H, H, k, k, s, pad)
+    oracle.set_threads(1)
+    t2 = time.perf_counter()
+    acc1 = oracle.conv_acc(ref["wint"].reshape(M, C, k, k), x.astype(np.int32), d, 0)
+    t3 = time.perf_counter()
+    oracle.set_threads(threads)
+    single = 2.0 * M * C * k * k * acc1.shape[1] / (t3 - t2) / 1e12
+    return dict(value=2.0 * macs / (t1 - t0) / 1e12, unit="TOPS", cores=threads, kind="oracle",
+                sample="all 20 layers of configs[3] on %d images (%.2f s wall on %d threads); one thread alone on "
+                       "layer3.1.conv1, one image: %.5f TOPS (%.2f s)" % (sample_batch, t1 - t0, threads, single, t3 - t2),
+                single_thread_value=single)
+
+
+def check_against_oracle(rm, oracle, torch, layers):
+    """First and last image of every layer: 4-bit codes of the timed launches against the oracle."""
+    for L in layers:
+        imgs = [0, BATCH - 1]
+        ref, acc, rs = oracle_reference(oracle, L, imgs)
+        _, _, q = oracle.epilogue(acc, rs, 0, ref["rowscale"], L["s_x"], None, True, L["inv"])
+        hw = L["OH"] * L["OH"]
+        Y = L["Y"].view(BATCH, hw, L["M"] // 2)[torch.tensor(imgs)].reshape(2 * hw, L["M"] // 2).cpu().numpy()
+        got = rm.unpack_u4(Y)  # [n][grouped row]
+        chk = np.empty_like(q)
+        chk[L["p"].perm] = got.T
+        if not np.array_equal(chk, q):
+            print("bench.py: GPU output of %s differs from the oracle" % L["name"], file=sys.stderr)
+            sys.exit(1)
+
+
+def time_block(torch, fns, iters, warm):
+    for i in range(warm):
+        fns[i % len(fns)]()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(iters):
+        fns[i % len(fns)]()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / iters  # microseconds per launch
+
+
+def other_configs(rm, si, torch, dev):
+    """configs[1], configs[2] (4-bit and fp32 output) and configs[4] with cold weights, timed as
+    blocks of back-to-back launches between two events (no oracle: parity is the tests' job)."""
+    out = {}
+    # configs[1]
+    c = si.CONFIGS[1]
+    rng = si.rng_for(1)
+    K = c["C"] * 9
+    W = si.weights_rowscaled(rng, c["M"], K)
+    scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(c["M"], *c["ratio"]))
+    p = rm.rmsmp_pack_weights(W, scheme, taps=9)
+    X = torch.from_numpy(rm.pack_u4(si.act_codes_u4(rng, (c["B"], 14, 14, c["C"])))).to(dev)
+    N = c["B"] * 196
+    Y = torch.empty((N, c["M"] // 2), dtype=torch.uint8, device=dev)
+    d = rm.ConvDesc(c["B"], c["C"], 14, 14, 3, 3, 1, 1)
+    f = rm.conv2d_launcher(p, X, d, rm.make_epilogue(0.05, 0, 4, None, True, rm.OUT_U4, 2.0), Y, None)
+    us = time_block(torch, [f], 1000, 50)
+    ops = 2.0 * c["M"] * K * N
+    out["configs[1] conv 256->256 3x3 batch 32, u4 out"] = dict(us=round(us, 3), tops=round(ops / us / 1e6, 1),
+                                                                frac_of_int8_peak=round(ops / us / 1e6 / INT8_MFMA_PEAK_TOPS, 4))
+    p.free()
+    # configs[2]
+    M, K, N = 3072, 768, 4096
+    rng = si.rng_for(2)
+    W = si.weights_bert(rng, M, K)
+    scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, 35, 60, 5))
+    xq, s_x, z = si.affine_u4_from_float(rng.standard_normal((N, K)))
+    p = rm.rmsmp_pack_weights(W, scheme)
+    X = torch.from_numpy(rm.pack_u4(xq)).to(dev)
+    ops = 2.0 * M * K * N
+    for kind, label in ((rm.OUT_U4, "u4 out"), (rm.OUT_FP32, "fp32 out")):
+        Y = (torch.empty((N, M // 2), dtype=torch.uint8, device=dev) if kind == rm.OUT_U4
+             else torch.empty((M, N), dtype=torch.float32, device=dev))
+        f = rm.gemm_launcher(p, X, N, rm.make_epilogue(s_x, z, 4, None, kind == rm.OUT_U4, kind, 2.0), Y)
+        us = time_block(torch, [f], 500, 30)
+        out["configs[2] BERT FFN-up 3072x768x4096, " + label] = dict(
+            us=round(us, 3), tops=round(ops / us / 1e6, 1), frac_of_int8_peak=round(ops / us / 1e6 / INT8_MFMA_PEAK_TOPS, 4))
+    p.free()
+    # configs[4]: enough packed copies (> the 256 MB last-level cache) that every launch streams from HBM
+    M = K = 4096
+    rng = si.rng_for(4)
+    W = si.weights_rowscaled(rng, M, K)
+    scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, 40, 50, 10))
+    packs = [rm.rmsmp_pack_weights(W, scheme) for _ in range(40)]
+    wbytes = sum(cnt * K * b for cnt, b in zip(packs[0].counts, (0.5, 0.5, 1.0)))
+    for N in (1, 8, 64):
+        X = torch.from_numpy(rm.pack_u4(si.act_codes_u4(rng, (N, K)))).to(dev)
+        Y = torch.empty((M, N), dtype=torch.float32, device=dev)
+        ep = rm.make_epilogue(0.05, 0, 4, None, False, rm.OUT_FP32, 1.0)
+        fns = [rm.gemm_launcher(pk, X, N, ep, Y) for pk in packs]
+        us = time_block(torch, fns, 400, 40)
+        out["configs[4] skinny 4096x4096 N=%d, cold weights" % N] = dict(
+            us=round(us, 3), tops=round(2.0 * M * K * N / us / 1e6, 2), weight_gbs=round(wbytes / us / 1e3, 1),
+            frac_of_hbm_peak=round(wbytes / us / 1e3 / HBM_PEAK_GBS, 4))
+    for pk in packs:
+        pk.free()
+    return out
+
+
+def traffic_from_profile(kernel_name):
+    """HBM bytes per launch of the dominant kernel as the committed rocprofv3 counter summary of this
+    workload states them (a counter cannot be read from inside this script); None when no summary
+    names this kernel."""
+    path = os.path.join(ROOT, "profiles", "resnet18_stack_dominant_kernel_traffic.txt")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    m = re.search(r"^kernel:\s*(.+)$", text, re.M)
+    t = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", text, re.M)
+    if not m or not t or m.group(1).strip() != kernel_name:
+        return None
+    return int(t.group(1))
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle (its timing and the in-run check)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the other configurations and the machine peaks")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (a known-size kernel to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE readings with)")
@@ -77,31 +242,33 @@ def main():
 
     import torch
     import paper_2111_00153_amd as rm
+    import synth_inputs as si
 
     dev = torch.device("cuda:0")
-    wl = make_conv_workload(1)
-    c = wl["cfg"]
-    M, K = c["M"], wl["K"]
-    OH = (c["H"] + 2 * c["pad"] - c["KH"]) // c["stride"] + 1
-    OW = (c["W"] + 2 * c["pad"] - c["KW"]) // c["stride"] + 1
-    N = c["B"] * OH * OW
-
     base = None
-    s_out = 0.5
+    inv_scales = None
     if not args.no_cpu_baseline:
-        base, ref, y = cpu_baseline(wl)
-        s_out = float(np.percentile(y, 99.9)) / 15.0
-    inv = np.float32(1.0 / s_out)
+        import oracle
+        base = cpu_baseline(oracle, si)
+    layers = make_stack(rm, si, torch, dev, BATCH)
+    if base is not None:
+        # output scales from the oracle's own output on the first and last image: s_out = 99.9th percentile / 15
+        inv_scales = []
+        for L in layers:
+            ref, acc, rs = oracle_reference(oracle, L, [0, BATCH - 1])
+            _, y, _ = oracle.epilogue(acc, rs, 0, ref["rowscale"], L["s_x"], None, True)
+            inv_scales.append(np.float32(15.0 / max(float(np.percentile(y, 99.9)), 1e-6)))
+        for L, inv in zip(layers, inv_scales):
+            L["inv"] = inv
+            L["ep"] = rm.make_epilogue(L["s_x"], 0, L["bits"], None, True, rm.OUT_U4, inv)
+            L["launch"] = rm.conv2d_launcher(L["p"], L["X"], L["d"], L["ep"], L["Y"], L["ws"])
+    launchers = [L["launch"] for L in layers]
+    total_ops = sum(L["ops"] for L in layers)
 
-    p = rm.rmsmp_pack_weights(wl["W"], wl["scheme"], taps=c["KH"] * c["KW"])
-    X = torch.from_numpy(rm.pack_u4(wl["x"])).to(dev)
-    Y = torch.empty((N, M // 2), dtype=torch.uint8, device=dev)
-    d = rm.ConvDesc(c["B"], c["C"], c["H"], c["W"], c["KH"], c["KW"], c["stride"], c["pad"])
-    ep = rm.make_epilogue(c["s_x"], 0, 4, None, True, rm.OUT_U4, inv)
-    ws_bytes = rm.rmsmp_conv2d_workspace_size(p, d, 4)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
+    def step():
+        for f in launchers:
+            f()
 
-    step = rm.conv2d_launcher(p, X, d, ep, Y, ws)  # arguments marshalled once; one call = one step
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -114,28 +281,33 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     gpu_ms = e0.elapsed_time(e1)
-    # the job's time is what the host saw between the two synchronizations
-    ms_per_step = wall * 1e3 / args.steps
-    ops = 2.0 * M * K * N
-    tops = ops / (ms_per_step * 1e-3) / 1e12
-    kern_ms = gpu_ms / args.steps
-    achieved = ops / (kern_ms * 1e-3) / 1e12
-    kernel, split = rm.rmsmp_debug_last_dispatch()
-    kernel_name = ("rmsmp::conv_wide_kernel<9, 8, %d, %d, %d, %d, false>" % split) if kernel == "lds_resident" else kernel
+    ms_per_step = wall * 1e3 / args.steps  # the job's time is what the host saw between the two synchronizations
+    tops = total_ops / (ms_per_step * 1e-3) / 1e12
 
     if base is not None:
-        # spot check of the timed configuration against the oracle (first images)
-        import oracle
-        n_img = 2
-        dd = oracle.conv_desc(n_img, c["C"], c["H"], c["W"], c["KH"], c["KW"], c["stride"], c["pad"])
-        acc = oracle.conv_acc(ref["wint"].reshape(M, c["C"], c["KH"], c["KW"]), wl["x"][:n_img].astype(np.int32), dd, 0)
-        _, _, q = oracle.epilogue(acc, oracle.rowsum(ref["wint"]), 0, ref["rowscale"], c["s_x"], None, True, inv)
-        got = rm.unpack_u4(Y[: n_img * OH * OW].cpu().numpy())  # [n][grouped row]
-        chk = np.empty_like(q)
-        chk[p.perm] = got.T
-        if not np.array_equal(chk, q):
-            print("bench.py: GPU output differs from the oracle", file=sys.stderr)
-            sys.exit(1)
+        check_against_oracle(rm, oracle, torch, layers)
+
+    # per-layer times: every layer alone, back to back, between two events
+    per_layer, families = {}, {}
+    for L in layers:
+        L["kernel"] = kernel_of(rm, L)
+    torch.cuda.synchronize()
+    for L in layers:
+        us = time_block(torch, [L["launch"]], 200, 10)
+        L["us"] = us
+        per_layer[L["name"]] = dict(us=round(us, 3), tops=round(L["ops"] / us / 1e6, 1), kernel=L["kernel"])
+        fam = families.setdefault(L["kernel"], dict(us=0.0, ops=0.0, launches=0))
+        fam["us"] += us
+        fam["ops"] += L["ops"]
+        fam["launches"] += 1
+    sum_us = sum(L["us"] for L in layers)
+    share = {k: round(v["us"] / sum_us, 4) for k, v in sorted(families.items(), key=lambda kv: -kv[1]["us"])}
+    dom_name = max(families, key=lambda k: families[k]["us"])
+    dom_layers = [L for L in layers if L["kernel"] == dom_name]
+    # the dominant kernel's average launch duration: its layers round-robin, back to back, between two events
+    dom_us = time_block(torch, [L["launch"] for L in dom_layers], 100 * len(dom_layers), 4 * len(dom_layers))
+    dom_ops = sum(L["ops"] for L in dom_layers) / len(dom_layers)
+    achieved = dom_ops / dom_us / 1e6
 
     out = {
         "metric": "effective int TOPS of row-wise mixed-scheme GEMM (% int8 MFMA peak), 1 GPU",
@@ -143,15 +315,24 @@ def main():
         "ms_per_step": round(ms_per_step, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "pct_of_int8_mfma_peak": round(100.0 * tops / INT8_MFMA_PEAK_TOPS, 2),
-        "config": {"workload": "configs[1]: ResNet-18 3x3 conv via im2col, batch 32, 256->256 ch, 14x14, s1 p1 "
-                               "(GEMM M=256 K=2304 N=6272), rows Fixed4:PoT4:Fixed8 = 60:35:5, uint4 activations, "
-                               "fused ReLU + uint4 requant",
-                   "rows_per_scheme": list(wl["counts"])},
+        "config": {"workload": "configs[3]: full ResNet-18 conv stack, batch 64, 224x224: 20 conv layers (232.1 GOP per step), "
+                               "conv1 Fixed-8 rows x int8 activations, the others rows Fixed4:PoT4:Fixed8 = 60:35:5 x uint4 "
+                               "activations, each one rmsmp_conv2d launch with fused ReLU + uint4 requant, back to back on one stream",
+                   "gop_per_step": round(total_ops / 1e9, 2), "launches_per_step": len(layers),
+                   "gpu_events_ms_per_step": round(gpu_ms / args.steps, 6)},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES,
-                     "kernel": kernel_name, "avg_launch_us": round(kern_ms * 1e3, 3)},
+                     "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4), "traffic": traffic_from_profile(dom_name),
+                     "kernel": dom_name, "avg_launch_us": round(dom_us, 3), "gop_per_launch": round(dom_ops / 1e9, 3),
+                     "layers": [L["name"] for L in dom_layers], "time_share_by_kernel": share},
+        "per_layer": per_layer,
         "cpu_baseline": base,
     }
+    if not args.no_extras:
+        out["other_configs"] = other_configs(rm, si, torch, dev)
+        mfma_tops, copy_gbs = rm.rmsmp_debug_measure_peaks()
+        out["measured_peaks"] = {"mfma_only_int8_tops": round(mfma_tops, 1), "stream_copy_gbs": round(copy_gbs, 1),
+                                 "note": "MFMA-only: 2 waves per SIMD issuing v_mfma_i32_32x32x32_i8 on registers; "
+                                         "stream copy: 1 GiB read + 1 GiB written by a plain copy kernel"}
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -159,7 +340,8 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
     print(json.dumps(out))
-    p.free()
+    for L in layers:
+        L["p"].free()
 
 
 if __name__ == "__main__":

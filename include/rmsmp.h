@@ -217,9 +217,9 @@ rmsmp_status rmsmp_ste_backward(const float* W, const float* alpha, const float*
  *   are shared out: pixel_blocks (2 or 4: 64 or 128 output pixels per wave), k_split (waves that
  *   share one output block, each taking every k_split-th K step), side_by_side (output blocks
  *   next to each other), tile_pairs (pairs of weight tiles per work-group);
- *   k_split * side_by_side * tile_pairs = 4.  The request applies to every later launch of the
- *   process where it fits the layer (otherwise the automatic choice stays); all zero returns
- *   to the automatic choice.  Not synchronized with concurrent launches.
+ *   k_split * side_by_side * tile_pairs = 4.  The request belongs to the calling thread: it
+ *   applies to every later launch from that thread where it fits the layer (otherwise the
+ *   automatic choice stays); all zero returns to the automatic choice.
  * rmsmp_debug_last_dispatch -- what the calling thread's last rmsmp_gemm / rmsmp_conv2d ran:
  *   out (HOST, 5 entries) = {kernel, pixel_blocks, k_split, side_by_side, tile_pairs} with kernel
  *   0 none, 1 general, 2 skinny (N <= 64), 3 small-channel rows, 4 first layer (3 channels,
@@ -229,6 +229,15 @@ rmsmp_status rmsmp_ste_backward(const float* W, const float* alpha, const float*
 rmsmp_status rmsmp_debug_set_wave_split(int32_t pixel_blocks, int32_t k_split, int32_t side_by_side,
                                         int32_t tile_pairs);
 rmsmp_status rmsmp_debug_last_dispatch(int32_t out[5]);
+
+/*
+ * Measurement hook for benchmarks (not part of the method): what the current device sustains
+ * with only int8 matrix instructions in flight (TOP/s, 2 ops per multiply-accumulate, operands
+ * in registers) and with only a copy kernel (GB/s, bytes read plus bytes written, 1 GiB each
+ * way).  Either pointer (HOST) may be NULL.  Allocates and frees 2 GiB of device memory and
+ * synchronizes the device: never call it on a hot path.  Errors: EHIP.
+ */
+rmsmp_status rmsmp_debug_measure_peaks(double* mfma_int8_tops, double* copy_gbs);
 
 #ifdef __cplusplus
 }

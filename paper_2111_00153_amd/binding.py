@@ -54,7 +54,7 @@ EXPORTS = ["rmsmp_last_error", "rmsmp_version", "rmsmp_ratio_counts", "rmsmp_ass
            "rmsmp_pack_weights", "rmsmp_free_packed", "rmsmp_packed_info", "rmsmp_unpack_codes",
            "rmsmp_pack_roundtrip_host", "rmsmp_gemm", "rmsmp_conv2d", "rmsmp_conv2d_workspace_size",
            "rmsmp_fake_quant_rows", "rmsmp_ste_backward", "rmsmp_debug_set_wave_split",
-           "rmsmp_debug_last_dispatch"]
+           "rmsmp_debug_last_dispatch", "rmsmp_debug_measure_peaks"]
 
 
 def _check(rc):
@@ -246,6 +246,13 @@ def rmsmp_debug_last_dispatch():
     out = (ctypes.c_int32 * 5)()
     _check(_lib.rmsmp_debug_last_dispatch(out))
     return KERNEL_NAMES[out[0]], tuple(int(v) for v in out[1:])
+
+
+def rmsmp_debug_measure_peaks():
+    """(MFMA-only int8 TOP/s, copy GB/s read + written) of the current device."""
+    a, b = ctypes.c_double(), ctypes.c_double()
+    _check(_lib.rmsmp_debug_measure_peaks(ctypes.byref(a), ctypes.byref(b)))
+    return float(a.value), float(b.value)
 
 
 # ---- storage helpers for callers (nibble packing of activation codes; no arithmetic of the method)

@@ -7,8 +7,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "librmsmp.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["csrc/pack_host.cpp", "csrc/kernels.hip", "csrc/patch_wide.hip", "csrc/conv_first.hip", "csrc/fakequant.hip", "csrc/api.hip"]
-HEADERS = ["csrc/rmsmp_internal.h", "csrc/device_common.h", "csrc/patch_wide.h", "../include/rmsmp.h"]
+SOURCES = ["csrc/pack_host.cpp", "csrc/kernels.hip", "csrc/patch_wide.hip", "csrc/conv_first.hip", "csrc/fakequant.hip", "csrc/peaks.hip", "csrc/api.hip"]
+HEADERS = ["csrc/rmsmp_internal.h", "csrc/device_common.h", "csrc/phase_stamps.h", "csrc/patch_wide.h", "../include/rmsmp.h"]
 # (filter taps, channels / 32) families of the wide LDS-resident kernel: csrc/patch_wide_inst.hip is
 # compiled once per family so that they build in parallel
 WIDE_FAMILIES = [(9, 2), (9, 4), (9, 8), (9, 16), (1, 2), (1, 4), (1, 8), (1, 16), (1, 24)]

@@ -242,10 +242,11 @@ static bool conv_is_implicit(const rmsmp_packed* Wp, const rmsmp_conv_desc* d, i
 rmsmp_status rmsmp_debug_set_wave_split(int32_t pixel_blocks, int32_t k_split, int32_t side_by_side, int32_t tile_pairs) {
   if (pixel_blocks < 0 || k_split < 0 || side_by_side < 0 || tile_pairs < 0)
     return fail(RMSMP_EINVAL, "debug_set_wave_split: negative value");
-  rmsmp::g_forced_split[0] = pixel_blocks;
-  rmsmp::g_forced_split[1] = k_split;
-  rmsmp::g_forced_split[2] = side_by_side;
-  rmsmp::g_forced_split[3] = tile_pairs;
+  int* split = rmsmp::forced_split();
+  split[0] = pixel_blocks;
+  split[1] = k_split;
+  split[2] = side_by_side;
+  split[3] = tile_pairs;
   return RMSMP_OK;
 }
 
@@ -253,6 +254,12 @@ rmsmp_status rmsmp_debug_last_dispatch(int32_t out[5]) {
   if (!out) return fail(RMSMP_EINVAL, "debug_last_dispatch: NULL out");
   const rmsmp::DispatchRecord& r = rmsmp::last_dispatch();
   out[0] = r.kernel, out[1] = r.xb, out[2] = r.ks, out[3] = r.nwt, out[4] = r.ms;
+  return RMSMP_OK;
+}
+
+rmsmp_status rmsmp_debug_measure_peaks(double* mfma_int8_tops, double* copy_gbs) {
+  hipError_t e = (hipError_t)rmsmp::measure_peaks(mfma_int8_tops, copy_gbs);
+  if (e != hipSuccess) return hip_fail(e, "debug_measure_peaks");
   return RMSMP_OK;
 }
 

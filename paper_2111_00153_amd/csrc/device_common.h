@@ -5,43 +5,13 @@
 #include <hip/hip_runtime.h>
 #include <type_traits>
 
+#include "phase_stamps.h"
 #include "rmsmp_internal.h"
 
 namespace rmsmp {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
-
-// Optional per-wave phase timestamps for tuning builds (-DRMSMP_PHASE_TIMING); compiled out
-// otherwise.  A stamp is one clock read parked in the first KiB of dynamic LDS (16 slots per
-// wave); the kernel copies the slots to g_phase_buf when it ends, so a stamp costs no memory
-// round trip where it is taken.
-#ifdef RMSMP_PHASE_TIMING
-__device__ unsigned long long* g_phase_buf = nullptr;
-constexpr int PHASE_LDS_BYTES = 1024;
-extern __shared__ __attribute__((aligned(16))) uint8_t phase_smem[];
-#define RMSMP_PHASE(id)                                                                                  \
-  do {                                                                                                   \
-    __builtin_amdgcn_sched_barrier(0);                                                                   \
-    if ((threadIdx.x & 63) == 0) ((unsigned long long*)phase_smem)[(threadIdx.x >> 6) * 16 + (id)] = clock64(); \
-    __builtin_amdgcn_sched_barrier(0);                                                                   \
-  } while (0)
-#define RMSMP_PHASE_FLUSH()                                                                              \
-  do {                                                                                                   \
-    if (g_phase_buf && (threadIdx.x & 63) == 0)                                                          \
-      for (int i_ = 0; i_ < 16; ++i_)                                                                    \
-        g_phase_buf[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + i_] =                                  \
-            ((unsigned long long*)phase_smem)[(threadIdx.x >> 6) * 16 + i_];                             \
-  } while (0)
-#else
-constexpr int PHASE_LDS_BYTES = 0;
-#define RMSMP_PHASE(id) \
-  do {                  \
-  } while (0)
-#define RMSMP_PHASE_FLUSH() \
-  do {                      \
-  } while (0)
-#endif
 
 // ---------------------------------------------------------------- operand decode
 
@@ -173,7 +143,6 @@ struct EpArgs {
   int64_t N, M;
   float act_scale, out_inv_scale;
   int zp, relu, out_kind;
-  bool stamps = false;  // tuning builds: this kernel reserved the stamp slots in LDS
 };
 
 __device__ __forceinline__ EpArgs pin_epilogue_args(const GemmArgs& a) {
@@ -292,7 +261,6 @@ __device__ __forceinline__ void finish_tiles(const EpArgs& a, int kind, const v1
       for (int j = 0; j < NB; ++j) v[j][r] -= c;
     }
   }
-  if (a.stamps) RMSMP_PHASE(8);
   float bias[16], m[16];
   const float fold = x16 ? 0.0625f : 1.0f;
 #pragma unroll
@@ -320,7 +288,6 @@ __device__ __forceinline__ void finish_tiles(const EpArgs& a, int kind, const v1
         if (r < n_rows && n[j] < a.N) as_global((float*)a.Y)[(int64_t)rm.orig(r) * a.N + n[j]] = y[j][r];
     return;
   }
-  if (a.stamps) RMSMP_PHASE(12);
   // with a positive output scale the clamp at code 0 already does what ReLU would (a negative y
   // rounds to a non-positive value), so the separate maximum is skipped
   const bool relu_q = relu && !(a.out_inv_scale > 0.0f);
@@ -339,7 +306,6 @@ __device__ __forceinline__ void finish_tiles(const EpArgs& a, int kind, const v1
         requant_block<false, false>(v[j], m, bias, a.out_inv_scale, packed[j]);
     }
   }
-  if (a.stamps) RMSMP_PHASE(13);
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
     if (n[j] >= a.N) continue;
@@ -351,7 +317,6 @@ __device__ __forceinline__ void finish_tiles(const EpArgs& a, int kind, const v1
       for (int b = 0; b < n_rows / 2; ++b) dst[b] = (uint8_t)(packed[j][b >> 2] >> (8 * (b & 3)));
     }
   }
-  if (a.stamps) RMSMP_PHASE(9);
 }
 
 __device__ __forceinline__ int lane_rows(int nvalid, int lane) {

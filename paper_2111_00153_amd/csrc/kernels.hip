@@ -309,16 +309,8 @@ static int launch_skinny_t(const GemmArgs& a, hipStream_t s) {
   const size_t xs = (size_t)SK_WAVES * 32 * NB * (SK_CHUNK * 16 + 8);
   const size_t xch = (size_t)SK_WAVES * NB * 16 * LANES * 4;
   const size_t lds = xs > xch ? xs : xch;
-  static bool allowed[64] = {false};
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return (int)e;
-  if (dev < 0 || dev >= 64) return (int)hipErrorInvalidDevice;
-  if (!allowed[dev]) {
-    e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<NB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return (int)e;
-    allowed[dev] = true;
-  }
+  static std::atomic<uint64_t> allowed{0};
+  if (const int rc = allow_large_lds((const void*)gemm_skinny_kernel<NB>, allowed)) return rc;
   hipLaunchKernelGGL(gemm_skinny_kernel<NB>, dim3((unsigned)a.w.n_tiles), dim3(SK_THREADS), lds, s, a);
   return (int)hipGetLastError();
 }
@@ -461,7 +453,22 @@ static int launch_conv_rows(const GemmArgs& a, hipStream_t s) {
   return (int)hipGetLastError();
 }
 
-int g_forced_split[4] = {0, 0, 0, 0};
+int* forced_split() {
+  static thread_local int split[4] = {0, 0, 0, 0};
+  return split;
+}
+int allow_large_lds(const void* kernel, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= 64) return (int)hipErrorInvalidDevice;
+  const uint64_t bit = (uint64_t)1 << dev;
+  if (done.load(std::memory_order_acquire) & bit) return 0;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (e != hipSuccess) return (int)e;
+  done.fetch_or(bit, std::memory_order_release);
+  return 0;
+}
 DispatchRecord& last_dispatch() {
   static thread_local DispatchRecord rec;
   return rec;

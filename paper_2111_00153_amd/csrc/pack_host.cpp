@@ -187,6 +187,17 @@ rmsmp_status pack_host(const float* W, int64_t M, int64_t K, const uint8_t* sche
       return RMSMP_EINVAL;
     }
     const float* w = W + r * K;
+    // a NaN or infinite weight has no level: refused whether or not the caller supplies alpha
+    float wmax = 0.0f;
+    bool finite = true;
+    for (int64_t k = 0; k < K; ++k) {
+      finite = finite && std::isfinite(w[k]);
+      wmax = std::max(wmax, std::fabs(w[k]));
+    }
+    if (!finite) {
+      *err = "pack_weights: non-finite weight in row " + std::to_string(r);
+      return RMSMP_EINVAL;
+    }
     float alpha;
     if (alpha_in) {
       alpha = alpha_in[r];
@@ -195,13 +206,7 @@ rmsmp_status pack_host(const float* W, int64_t M, int64_t K, const uint8_t* sche
         return RMSMP_EINVAL;
       }
     } else {
-      alpha = 0.0f;
-      for (int64_t k = 0; k < K; ++k) alpha = std::max(alpha, std::fabs(w[k]));
-      if (!std::isfinite(alpha)) {
-        *err = "pack_weights: non-finite weight in row " + std::to_string(r);
-        return RMSMP_EINVAL;
-      }
-      if (alpha == 0.0f) alpha = 1.0f;
+      alpha = wmax == 0.0f ? 1.0f : wmax;
     }
     hp->counts[scheme[r]] += 1;
     int8_t* q = wint.data() + r * K;

@@ -628,7 +628,6 @@ __device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGe
     for (int u = 0; u < pw_batch(TAPS); ++u) pl.pw[u] = wide_load_piece<CPT>(pl, u * (LANES * KS * NWT * MS) + (int)threadIdx.x);
   }
   EpArgs ea = pin_epilogue_args(a);
-  ea.stamps = PHASE_LDS_BYTES != 0;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n_pairs = (a.w.n_tiles + 1) / 2;
   // Pair y is tile y and tile n_tiles-1-y: tiles are sorted by class, so a table-decoded tile is
@@ -665,23 +664,13 @@ struct WidePlan {
   int cpt = 0;  // K steps of 32 channels staged at a time (the kernel family)
 };
 
-// Dynamic LDS above 64 KiB must be allowed per kernel once (per device); remember what was set.
 template <int TAPS, int CPT, int XB, int KS, int NWT, int MS, bool DEEP>
 inline int launch_wide_t(const WidePlan& p, hipStream_t s) {
   if constexpr (CPT % KS != 0 || TAPS * (CPT / KS) < 2) {
     return (int)hipErrorInvalidValue;
   } else {
-    static bool allowed[64] = {false};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return (int)e;
-    if (dev < 0 || dev >= 64) return (int)hipErrorInvalidDevice;
-    if (!allowed[dev]) {
-      e = hipFuncSetAttribute((const void*)conv_wide_kernel<TAPS, CPT, XB, KS, NWT, MS, DEEP>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-      if (e != hipSuccess) return (int)e;
-      allowed[dev] = true;
-    }
+    static std::atomic<uint64_t> allowed{0};
+    if (const int rc = allow_large_lds((const void*)conv_wide_kernel<TAPS, CPT, XB, KS, NWT, MS, DEEP>, allowed)) return rc;
     hipLaunchKernelGGL((conv_wide_kernel<TAPS, CPT, XB, KS, NWT, MS, DEEP>), dim3(p.blocks), dim3(LANES * KS * NWT * MS), p.lds, s, p.a, p.g);
     return (int)hipGetLastError();
   }

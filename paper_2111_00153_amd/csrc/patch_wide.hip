@@ -192,9 +192,10 @@ static int launch_wide(const WidePlan& p, hipStream_t s) {
 int try_launch_wide(const GemmArgs& a, void* stream, bool* applied) {
   WidePlan plan;
   *applied = wide_kernel_applies(a, &plan);
-  if (*applied && g_forced_split[0] > 0) {
+  const int* forced = forced_split();
+  if (*applied && forced[0] > 0) {
     WidePlan p2;
-    if (wide_plan_mode(plan.a, plan.cpt * KSTEP, g_forced_split[0], g_forced_split[1], g_forced_split[2], g_forced_split[3], &p2)) plan = p2;
+    if (wide_plan_mode(plan.a, plan.cpt * KSTEP, forced[0], forced[1], forced[2], forced[3], &p2)) plan = p2;
   }
   if (!*applied) return 0;
   DispatchRecord& rec = last_dispatch();

@@ -1,6 +1,7 @@
 // Internal declarations shared by the host packer, the kernels and the C-ABI glue.
 // Not installed; the public interface is include/rmsmp.h.
 #pragma once
+#include <atomic>
 #include <cstddef>
 #include <cstdint>
 #include <string>
@@ -149,14 +150,15 @@ struct SteArgs {
 int launch_fake_quant_rows(const FakeQuantArgs& a, void* stream);
 int launch_ste_backward(const SteArgs& a, void* stream);
 
-// Test hooks.  g_forced_split: a wave split {pixel blocks per wave, K split, 128-pixel blocks, tile
-// pairs} the LDS-resident kernel should use where it fits the layer (all zero: automatic).
+// Test hooks.  forced_split(): a wave split {pixel blocks per wave, K split, pixel blocks side by
+// side, tile pairs} the LDS-resident kernel should use where it fits the layer (all zero:
+// automatic); like last_dispatch() it belongs to the calling thread.
 // last_dispatch(): which kernel the calling thread's last launch_gemm went to.
 struct DispatchRecord {
   int kernel = 0;  // 0 none, 1 general, 2 skinny, 3 small-channel rows, 4 first layer, 5 LDS-resident
   int xb = 0, ks = 0, nwt = 0, ms = 0;
 };
-extern int g_forced_split[4];
+int* forced_split();
 DispatchRecord& last_dispatch();
 
 // Kernel launchers (kernels.hip).  Return hipError_t as int.
@@ -167,6 +169,13 @@ int try_launch_wide(const GemmArgs& a, void* stream, bool* applied);
 // First-layer kernel (conv_first.hip): 3 input channels, 8-bit activations, stride 2; same convention.
 int try_launch_conv_first(const GemmArgs& a, void* stream, bool* applied);
 int launch_im2col(const Im2colArgs& a, void* stream);
+// Machine rates (peaks.hip): MFMA-only int8 TOP/s and copy GB/s (read + written) of the current device.
+int measure_peaks(double* mfma_tops, double* copy_gbs);
+
+// Dynamic LDS above 64 KiB must be allowed per kernel once on every device.  `done` is the
+// kernel's own bit mask of devices that have it (one per launcher, a function-local static):
+// two threads that race on the first launch both set the attribute, which is harmless.
+int allow_large_lds(const void* kernel, std::atomic<uint64_t>& done);
 
 }  // namespace rmsmp
 

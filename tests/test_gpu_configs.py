@@ -86,7 +86,7 @@ def test_config4_skinny_gemm(rm, oracle, N):
     p.free()
 
 
-def _resnet_layer(rm, oracle, idx, B, n_samples):
+def _resnet_layer(rm, oracle, idx, B, n_samples, structured=False):
     name, C, M, k, s, pad, H = si.RESNET18_CONVS[idx]
     rng = si.rng_for(3, idx)
     K = C * k * k
@@ -112,6 +112,21 @@ def _resnet_layer(rm, oracle, idx, B, n_samples):
     # make sure image borders, the first / last pixel and every row class are among the samples
     ns[:4] = (0, N - 1, OW - 1, N - OW)
     ms[:M if M < n_samples else n_samples] = np.arange(M)[:n_samples]
+    if structured:
+        # Whole pixel tiles of the launch geometry the library picks for this layer, every row of each:
+        # the first, a middle and the last (ragged) tile, and the tiles around the first and the last
+        # image boundary.  The tile width is the largest any kernel here uses (512 pixels); a narrower
+        # launch tile divides it, so whole launch tiles are covered whatever the split.
+        tile = 512
+        n_tiles = (N + tile - 1) // tile
+        hw = OH * OW
+        want = {0, n_tiles // 2, n_tiles - 1, (hw - 1) // tile, hw // tile, ((B - 1) * hw - 1) // tile, ((B - 1) * hw) // tile}
+        cols = np.concatenate([np.arange(t * tile, min(N, (t + 1) * tile)) for t in sorted(t for t in want if 0 <= t < n_tiles)])
+        # every row of every weight tile (the padded tail of each class's last tile included)
+        mm, nn = np.meshgrid(np.arange(M), cols, indexing="ij")
+        ms = np.concatenate([ms, mm.ravel()])
+        ns = np.concatenate([ns, nn.ravel()])
+        n_samples = ms.size
     acc_s = oracle.conv_acc_at(wint4, x.astype(np.int32), od, ms, ns, 0)
     rs = oracle.rowsum(ref["wint"])
     # the oracle's epilogue works on whole rows: feed it the samples of each row in turn
@@ -149,9 +164,11 @@ def _resnet_layer(rm, oracle, idx, B, n_samples):
 
 @pytest.mark.parametrize("idx", range(len(si.RESNET18_CONVS)))
 def test_config3_resnet18_layer_batch64_sampled(rm, oracle, idx):
-    """Every convolution of the ResNet-18 stack at batch 64 and 224x224 input geometry, 4000 sampled
-    outputs per layer against the oracle's direct convolution (accumulators and 4-bit codes)."""
-    _resnet_layer(rm, oracle, idx, 64, 4000)
+    """Every convolution of the ResNet-18 stack at batch 64 and 224x224 input geometry against the
+    oracle's direct convolution (accumulators and 4-bit codes): 4000 random outputs per layer, plus
+    every row of whole pixel tiles -- the first, a middle and the last one and those that straddle
+    an image boundary."""
+    _resnet_layer(rm, oracle, idx, 64, 4000, structured=True)
 
 
 @pytest.mark.parametrize("idx", [0, 5, 7, 12, 16])

@@ -160,6 +160,15 @@ def test_argument_errors(rm):
     assert e.value.code == 2
     with pytest.raises(rm.RmsmpError):
         rm.rmsmp_pack_roundtrip_host(W, np.zeros(4, np.uint8), alpha=np.array([1, 0, 1, 1], np.float32))
+    # a weight that is not a number has no level, whether alpha is the row maximum or the caller's
+    for bad in (np.nan, np.inf, -np.inf):
+        Wb = W.copy()
+        Wb[2, 5] = bad
+        for alpha in (None, np.ones(4, np.float32)):
+            for scheme in (0, 1, 2):
+                with pytest.raises(rm.RmsmpError) as e:
+                    rm.rmsmp_pack_roundtrip_host(Wb, np.full(4, scheme, np.uint8), alpha=alpha)
+                assert e.value.code == 1
 
 
 def test_nibble_helpers(rm):
