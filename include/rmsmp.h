@@ -183,6 +183,28 @@ rmsmp_status rmsmp_conv2d_workspace_size(const rmsmp_packed* Wp, const rmsmp_con
                                          int32_t act_bits, size_t* bytes);
 
 /*
+ * rmsmp_conv2d for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * rmsmp_conv2d, minus the workspace: layers that need one (see rmsmp_conv2d) materialise their
+ * im2col matrix in a buffer of RMSMP_STATIC_WORKSPACE_BYTES that is part of the library's device
+ * image; every GPU the library runs on holds its own copy until the process ends.  The call
+ * allocates and frees nothing and calls no allocating library routine.
+ *   - A layer whose rmsmp_conv2d_workspace_size() exceeds RMSMP_STATIC_WORKSPACE_BYTES is
+ *     refused with EWORKSPACE and nothing is launched; use rmsmp_conv2d with your own buffer.
+ *   - All calls on one GPU share that GPU's buffer, which keeps the last call's contents (every
+ *     byte a call reads it has written first, so nothing needs clearing).  Calls that may overlap
+ *     on one GPU -- different streams, different threads -- race on it: keep them on one stream.
+ * rmsmp_init() looks the buffer's device address up for the current device (once per device is
+ * enough; the first rmsmp_conv2d_static_workspace call on a device does it otherwise).
+ * Errors: as rmsmp_conv2d, plus EHIP from the address look-up.
+ */
+#define RMSMP_STATIC_WORKSPACE_BYTES (16u << 20)
+rmsmp_status rmsmp_init(void);
+rmsmp_status rmsmp_conv2d_static_workspace(const rmsmp_packed* Wp, const void* X,
+                                           const rmsmp_conv_desc* d, const rmsmp_epilogue* ep,
+                                           void* Y, void* stream);
+
+/*
  * Weight side of one quantization-aware training step (Alg. 1, loop body), on the device.
  *
  * rmsmp_fake_quant_rows -- forward: What = proj_S(W).  Row r is projected on the level set of

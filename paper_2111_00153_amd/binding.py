@@ -54,7 +54,7 @@ EXPORTS = ["rmsmp_last_error", "rmsmp_version", "rmsmp_ratio_counts", "rmsmp_ass
            "rmsmp_pack_weights", "rmsmp_free_packed", "rmsmp_packed_info", "rmsmp_unpack_codes",
            "rmsmp_pack_roundtrip_host", "rmsmp_gemm", "rmsmp_conv2d", "rmsmp_conv2d_workspace_size",
            "rmsmp_fake_quant_rows", "rmsmp_ste_backward", "rmsmp_debug_set_wave_split",
-           "rmsmp_debug_last_dispatch", "rmsmp_debug_measure_peaks"]
+           "rmsmp_debug_last_dispatch", "rmsmp_debug_measure_peaks", "rmsmp_init", "rmsmp_conv2d_static_workspace"]
 
 
 def _check(rc):
@@ -190,6 +190,18 @@ def rmsmp_conv2d(p, X, d, ep, Y, workspace=None, stream=None):
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(_lib.rmsmp_conv2d(p.handle, _dev(X), ctypes.byref(d), ctypes.byref(ep), _dev(Y), _dev(workspace),
                              ctypes.c_size_t(wbytes), _stream(stream)))
+
+
+STATIC_WORKSPACE_BYTES = 16 << 20  # RMSMP_STATIC_WORKSPACE_BYTES
+
+
+def rmsmp_init():
+    _check(_lib.rmsmp_init())
+
+
+def rmsmp_conv2d_static_workspace(p, X, d, ep, Y, stream=None):
+    _check(_lib.rmsmp_conv2d_static_workspace(p.handle, _dev(X), ctypes.byref(d), ctypes.byref(ep), _dev(Y),
+                                              _stream(stream)))
 
 
 def conv2d_launcher(p, X, d, ep, Y, workspace=None, stream=None):

@@ -1,6 +1,7 @@
 // C-ABI glue of librmsmp: argument checking, device memory of packed layers, kernel dispatch.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstring>
 #include <new>
 #include <string>
@@ -22,6 +23,27 @@ rmsmp_status hip_fail(hipError_t e, const char* what) {
 }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Workspace of rmsmp_conv2d_static_workspace.  In host code the array's name is only a handle
+// for hipGetSymbolAddress, never an address: kernels get the pointer that call returns for the
+// device they run on (each GPU has its own copy of the array at its own address).
+static __device__ __align__(256) uint8_t scratch[RMSMP_STATIC_WORKSPACE_BYTES];
+std::atomic<void*> g_scratch_ptr[64];
+
+rmsmp_status static_workspace(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= 64) return fail(RMSMP_EUNSUPPORTED, "static workspace: device ordinal above 63");
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress(static workspace)");
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return RMSMP_OK;
+}
 
 rmsmp_status check_epilogue(const rmsmp_epilogue* ep, int64_t M) {
   if (!ep) return fail(RMSMP_EINVAL, "epilogue is NULL");
@@ -333,6 +355,29 @@ rmsmp_status rmsmp_conv2d(const rmsmp_packed* Wp, const void* X, const rmsmp_con
   hipError_t e = (hipError_t)rmsmp::launch_gemm(a, stream);
   if (e != hipSuccess) return hip_fail(e, "conv2d: kernel launch");
   return RMSMP_OK;
+}
+
+rmsmp_status rmsmp_init(void) {
+  void* ws = nullptr;
+  return static_workspace(&ws);
+}
+
+rmsmp_status rmsmp_conv2d_static_workspace(const rmsmp_packed* Wp, const void* X, const rmsmp_conv_desc* d,
+                                           const rmsmp_epilogue* ep, void* Y, void* stream) {
+  if (!Wp) return fail(RMSMP_EINVAL, "conv2d: NULL packed weights");
+  if (!ep) return fail(RMSMP_EINVAL, "epilogue is NULL");
+  size_t need = 0;
+  rmsmp_status st = rmsmp_conv2d_workspace_size(Wp, d, ep->act_bits, &need);
+  if (st != RMSMP_OK) return st;
+  if (need == 0) return rmsmp_conv2d(Wp, X, d, ep, Y, nullptr, 0, stream);
+  if (need > (size_t)RMSMP_STATIC_WORKSPACE_BYTES)
+    return fail(RMSMP_EWORKSPACE, "conv2d_static_workspace: this layer needs " + std::to_string(need) +
+                                      " bytes of workspace, the static one holds " +
+                                      std::to_string((size_t)RMSMP_STATIC_WORKSPACE_BYTES));
+  void* ws = nullptr;
+  st = static_workspace(&ws);
+  if (st != RMSMP_OK) return st;
+  return rmsmp_conv2d(Wp, X, d, ep, Y, ws, (size_t)RMSMP_STATIC_WORKSPACE_BYTES, stream);
 }
 
 rmsmp_status rmsmp_fake_quant_rows(const float* W, int64_t M, int64_t K, const uint8_t* scheme, const float* alpha,
