@@ -217,6 +217,33 @@ def epilogue(acc, rowsum_, z, rowscale, s_x, bias=None, relu=False, inv_s_out=No
     return acc_c, y, q
 
 
+def epilogue_gelu(acc, rowsum_, z, rowscale, s_x, bias, inv_s_out, z_out):
+    """Zero-point correction, per-row dequant, bias, GELU and affine 4-bit requant.
+
+    Returns (g fp32, q uint8), q one code per element."""
+    acc = _i32(acc)
+    M, N = acc.shape
+    rs, sc = _i32(rowsum_), _f32(rowscale)
+    b = None if bias is None else _f32(bias)
+    g = np.empty((M, N), np.float32)
+    q = np.empty((M, N), np.uint8)
+    _L().oracle_epilogue_gelu(_p(acc, ctypes.c_int32), ctypes.c_int64(M), ctypes.c_int64(N),
+                              _p(rs, ctypes.c_int32), ctypes.c_int32(z), _p(sc, ctypes.c_float),
+                              ctypes.c_float(s_x), _p(b, ctypes.c_float), ctypes.c_float(inv_s_out),
+                              ctypes.c_int32(z_out), _p(g, ctypes.c_float), _p(q, ctypes.c_uint8))
+    return g, q
+
+
+def gelu_codes(y, inv_s_out, z_out):
+    """GELU and its affine 4-bit code for a list of fp32 pre-activations.  Returns (g fp32, q uint8)."""
+    y = _f32(y).ravel()
+    g = np.empty(y.size, np.float32)
+    q = np.empty(y.size, np.uint8)
+    _L().oracle_gelu_codes(_p(y, ctypes.c_float), ctypes.c_int64(y.size), ctypes.c_float(inv_s_out),
+                           ctypes.c_int32(z_out), _p(g, ctypes.c_float), _p(q, ctypes.c_uint8))
+    return g, q
+
+
 def gemm_f64(what, xq, s_x, z=0, bias=None, relu=False):
     """The plain float64 definition sum_k what * (s_x*(xq - z)) (+bias, ReLU)."""
     what = np.ascontiguousarray(what, dtype=np.float64)

@@ -358,6 +358,64 @@ void oracle_epilogue(const int32_t* acc, int64_t M, int64_t N, const int32_t* ro
   }
 }
 
+/* GELU epilogue of the feed-forward up-projection of a transformer layer (the BERT-base
+ * workload of Section 4.1 / Table 5; the paper names the model, not its activation quantizer):
+ * the activation of BERT is GELU(y) = y * Phi(y), Phi the standard normal distribution
+ * function, Phi(y) = (1 + erf(y / sqrt 2)) / 2 = erfc(-y / sqrt 2) / 2 (the second form keeps
+ * its relative accuracy in the negative tail, where the first cancels), and its output -- signed, bounded below by about
+ * -0.17 -- goes to the next layer as an unsigned 4-bit code with a zero point, the same
+ * affine activation format the up-projection reads.
+ *
+ * oracle_gelu_f32: the definition, evaluated in float64 from the fp32 argument and rounded to
+ * fp32 once. */
+float oracle_gelu_f32(float y) {
+  const double x = (double)y;
+  return (float)(0.5 * x * erfc(-x / sqrt(2.0)));
+}
+
+/* For every (r, n), in fp32 with each operation rounded on its own:
+ *   a = acc - z * rowsum[r] ; m = rowscale[r] * s_x ; y = (float)a * m ; y += bias[r]
+ *   g = GELU(y)                                        (oracle_gelu_f32)
+ *   q = clamp(rint(g * inv_s_out) + z_out, 0, 15)      (round-half-to-even)
+ * g_out and q_out are each optional; q is one code per byte. */
+void oracle_epilogue_gelu(const int32_t* acc, int64_t M, int64_t N, const int32_t* rowsum, int32_t z,
+                          const float* rowscale, float s_x, const float* bias, float inv_s_out,
+                          int32_t z_out, float* g_out, uint8_t* q_out) {
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < M; ++r) {
+    float m = rowscale[r] * s_x;
+    for (int64_t n = 0; n < N; ++n) {
+      int32_t a = acc[r * N + n] - z * rowsum[r];
+      float y = (float)a * m;
+      if (bias) y = y + bias[r];
+      float g = oracle_gelu_f32(y);
+      if (g_out) g_out[r * N + n] = g;
+      if (q_out) {
+        float t = g * inv_s_out;
+        float c = rintf(t) + (float)z_out;
+        c = fminf(fmaxf(c, 0.0f), 15.0f);
+        q_out[r * N + n] = (uint8_t)c;
+      }
+    }
+  }
+}
+
+/* The same quantizer applied to a plain list of pre-activations y (no accumulator in front):
+ * used to tabulate code(y) when thresholds are checked. */
+void oracle_gelu_codes(const float* y, int64_t count, float inv_s_out, int32_t z_out, float* g_out,
+                       uint8_t* q_out) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < count; ++i) {
+    float g = oracle_gelu_f32(y[i]);
+    if (g_out) g_out[i] = g;
+    if (q_out) {
+      float c = rintf(g * inv_s_out) + (float)z_out;
+      c = fminf(fmaxf(c, 0.0f), 15.0f);
+      q_out[i] = (uint8_t)c;
+    }
+  }
+}
+
 /* The plain definition in float64, with no integer factorisation at all:
  *   y64[r][n] = sum_k what[r][k] * ( s_x * (xq[n][k] - z) ) (+ bias, ReLU).
  * Used to check that the factorised fp32 epilogue stays within the stated
