@@ -128,6 +128,12 @@ rmsmp_status rmsmp_pack_roundtrip_host(const float* W, int64_t M, int64_t K, con
  *   out_kind 0: Y = a                                              int32
  *   out_kind 1: y = float(a) * (rowscale[r] * act_scale); y += bias[r]; relu -> Y = y   fp32
  *   out_kind 2: q = clamp(round(y * out_inv_scale), 0, 15)          4-bit code, nibble-packed
+ *   out_kind 3: g = GELU(y) = y * Phi(y), Phi the standard normal distribution function, taken
+ *               in float64 and rounded to fp32 once (relu must be 0);
+ *               q = clamp(round(g * out_inv_scale) + out_zero_point, 0, 15)   4-bit code
+ *               -- the activation between the two feed-forward projections of a transformer
+ *               layer (the BERT-base workload of Section 4.1), handed on in the affine 4-bit
+ *               activation format (real value = s_out * (code - out_zero_point)).
  * Every fp32 operation is rounded on its own (no fused multiply-add); round = half-to-even.
  */
 typedef struct {
@@ -136,8 +142,9 @@ typedef struct {
   int32_t act_bits;       /* 4: unsigned codes, two per byte; 8: signed int8 codes */
   const float* bias;      /* DEVICE fp32 [M], original row order, or NULL */
   int32_t relu;           /* 0 or 1 */
-  int32_t out_kind;       /* 0, 1 or 2 (see above) */
-  float out_inv_scale;    /* 1/s_out, used by out_kind 2 */
+  int32_t out_kind;       /* 0, 1, 2 or 3 (see above) */
+  float out_inv_scale;    /* 1/s_out, used by out_kind 2 and 3; positive and finite for out_kind 3 */
+  int32_t out_zero_point; /* 0..15, used by out_kind 3 */
 } rmsmp_epilogue;
 
 /*
@@ -148,7 +155,7 @@ typedef struct {
  *      act_bits 8 -> K int8 per column.  The K index is the one W was given in.  16-byte aligned.
  *   Y  DEVICE, caller-allocated:
  *        out_kind 0/1: [M][N] row-major, original row order (int32 / fp32)
- *        out_kind 2:   [N][M/2] bytes; column n, grouped row g in byte g/2 (even g low nibble);
+ *        out_kind 2/3: [N][M/2] bytes; column n, grouped row g in byte g/2 (even g low nibble);
  *                      M must be even.  This is exactly the X layout of a following layer.
  *   stream  hipStream_t as void*.  Asynchronous; no allocation; no workspace needed.
  * Errors: EINVAL, ESHAPE (N < 0, odd K with 4-bit codes, ...), EHIP.  N == 0 is a no-op.
@@ -168,7 +175,7 @@ typedef struct {
  *   Wp  packed with K = C*KH*KW and taps = KH*KW.
  *   X   DEVICE activation codes, NHWC: [B][H][W][C] (4-bit: C/2 bytes per pixel, C even).
  *       Pixels outside the image count as real value 0, i.e. code act_zero_point.
- *   Y   out_kind 0/1: [M][B*OH*OW];  out_kind 2: [B][OH][OW][M/2] bytes (NHWC, grouped rows).
+ *   Y   out_kind 0/1: [M][B*OH*OW];  out_kind 2/3: [B][OH][OW][M/2] bytes (NHWC, grouped rows).
  *   workspace  DEVICE scratch of at least rmsmp_conv2d_workspace_size() bytes, or NULL when
  *       that size is 0.  Layers whose C is a multiple of 16, and 8-bit layers with at
  *       most 4 input channels (a network's first layer), run without workspace: the
@@ -251,6 +258,17 @@ rmsmp_status rmsmp_ste_backward(const float* W, const float* alpha, const float*
 rmsmp_status rmsmp_debug_set_wave_split(int32_t pixel_blocks, int32_t k_split, int32_t side_by_side,
                                         int32_t tile_pairs);
 rmsmp_status rmsmp_debug_last_dispatch(int32_t out[5]);
+
+/*
+ * Test hook that needs no GPU: the break points the kernels use for out_kind 3.  As a function
+ * of the fp32 pre-activation y the code is piecewise constant: for y >= *y_split it is the
+ * largest c with rise[c] <= y; for y < *y_split it is *fall_base plus the number of j < *n_fall
+ * with y <= fall[j].  rise, fall: HOST, 16 floats each (-inf / +inf where a code is always /
+ * never reached).  Errors: EINVAL.
+ */
+rmsmp_status rmsmp_debug_gelu_breakpoints(float out_inv_scale, int32_t out_zero_point, float rise[16],
+                                          float fall[16], float* y_split, int32_t* fall_base,
+                                          int32_t* n_fall);
 
 /*
  * Measurement hook for benchmarks (not part of the method): what the current device sustains

@@ -16,7 +16,7 @@ import torch  # noqa: F401
 from . import build as _build
 
 FIXED4, POT4, FIXED8 = 0, 1, 2
-OUT_INT32, OUT_FP32, OUT_U4 = 0, 1, 2
+OUT_INT32, OUT_FP32, OUT_U4, OUT_GELU_U4 = 0, 1, 2, 3
 
 _STATUS = {0: "OK", 1: "EINVAL", 2: "ESHAPE", 3: "ENOMEM", 4: "EHIP", 5: "EUNSUPPORTED", 6: "EWORKSPACE"}
 
@@ -30,7 +30,7 @@ class RmsmpError(RuntimeError):
 class Epilogue(ctypes.Structure):
     _fields_ = [("act_scale", ctypes.c_float), ("act_zero_point", ctypes.c_int32), ("act_bits", ctypes.c_int32),
                 ("bias", ctypes.c_void_p), ("relu", ctypes.c_int32), ("out_kind", ctypes.c_int32),
-                ("out_inv_scale", ctypes.c_float)]
+                ("out_inv_scale", ctypes.c_float), ("out_zero_point", ctypes.c_int32)]
 
 
 class ConvDesc(ctypes.Structure):
@@ -54,7 +54,7 @@ EXPORTS = ["rmsmp_last_error", "rmsmp_version", "rmsmp_ratio_counts", "rmsmp_ass
            "rmsmp_pack_weights", "rmsmp_free_packed", "rmsmp_packed_info", "rmsmp_unpack_codes",
            "rmsmp_pack_roundtrip_host", "rmsmp_gemm", "rmsmp_conv2d", "rmsmp_conv2d_workspace_size",
            "rmsmp_fake_quant_rows", "rmsmp_ste_backward", "rmsmp_debug_set_wave_split",
-           "rmsmp_debug_last_dispatch", "rmsmp_debug_measure_peaks", "rmsmp_init", "rmsmp_conv2d_static_workspace"]
+           "rmsmp_debug_last_dispatch", "rmsmp_debug_measure_peaks", "rmsmp_init", "rmsmp_conv2d_static_workspace", "rmsmp_debug_gelu_breakpoints"]
 
 
 def _check(rc):
@@ -170,10 +170,10 @@ def rmsmp_pack_roundtrip_host(W, scheme, alpha=None, taps=1, in_perm=None):
 
 
 def make_epilogue(act_scale=1.0, act_zero_point=0, act_bits=4, bias=None, relu=False, out_kind=OUT_INT32,
-                  out_inv_scale=1.0):
+                  out_inv_scale=1.0, out_zero_point=0):
     return Epilogue(float(act_scale), int(act_zero_point), int(act_bits),
                     None if bias is None else bias.data_ptr(), 1 if relu else 0, int(out_kind),
-                    float(out_inv_scale))
+                    float(out_inv_scale), int(out_zero_point))
 
 
 def rmsmp_gemm(p, X, N, ep, Y, stream=None):
@@ -258,6 +258,15 @@ def rmsmp_debug_last_dispatch():
     out = (ctypes.c_int32 * 5)()
     _check(_lib.rmsmp_debug_last_dispatch(out))
     return KERNEL_NAMES[out[0]], tuple(int(v) for v in out[1:])
+
+
+def rmsmp_debug_gelu_breakpoints(out_inv_scale, out_zero_point):
+    """No GPU needed.  dict(rise[16], fall[16], y_split, fall_base, n_fall) of the GELU epilogue."""
+    rise, fall = np.empty(16, np.float32), np.empty(16, np.float32)
+    ys, fb, nf = ctypes.c_float(), ctypes.c_int32(), ctypes.c_int32()
+    _check(_lib.rmsmp_debug_gelu_breakpoints(ctypes.c_float(out_inv_scale), ctypes.c_int32(out_zero_point), _ptr(rise),
+                                             _ptr(fall), ctypes.byref(ys), ctypes.byref(fb), ctypes.byref(nf)))
+    return dict(rise=rise, fall=fall, y_split=float(ys.value), fall_base=int(fb.value), n_fall=int(nf.value))
 
 
 def rmsmp_debug_measure_peaks():

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "librmsmp.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["csrc/pack_host.cpp", "csrc/kernels.hip", "csrc/patch_wide.hip", "csrc/conv_first.hip", "csrc/fakequant.hip", "csrc/peaks.hip", "csrc/api.hip"]
+SOURCES = ["csrc/pack_host.cpp", "csrc/gelu_host.cpp", "csrc/kernels.hip", "csrc/patch_wide.hip", "csrc/conv_first.hip", "csrc/fakequant.hip", "csrc/peaks.hip", "csrc/api.hip"]
 HEADERS = ["csrc/rmsmp_internal.h", "csrc/device_common.h", "csrc/phase_stamps.h", "csrc/patch_wide.h", "../include/rmsmp.h"]
 # (filter taps, channels / 32) families of the wide LDS-resident kernel: csrc/patch_wide_inst.hip is
 # compiled once per family so that they build in parallel

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <cmath>
 #include <cstring>
 #include <new>
 #include <string>
@@ -48,14 +49,35 @@ rmsmp_status static_workspace(void** out) {
 rmsmp_status check_epilogue(const rmsmp_epilogue* ep, int64_t M) {
   if (!ep) return fail(RMSMP_EINVAL, "epilogue is NULL");
   if (ep->act_bits != 4 && ep->act_bits != 8) return fail(RMSMP_EINVAL, "act_bits must be 4 or 8");
-  if (ep->out_kind < 0 || ep->out_kind > 2) return fail(RMSMP_EINVAL, "out_kind must be 0, 1 or 2");
+  if (ep->out_kind < 0 || ep->out_kind > 3) return fail(RMSMP_EINVAL, "out_kind must be 0, 1, 2 or 3");
+  if (ep->out_kind == 3) {
+    if (ep->relu != 0) return fail(RMSMP_EINVAL, "out_kind 3 applies GELU: relu must be 0");
+    if (!(ep->out_inv_scale > 0.0f) || !std::isfinite(ep->out_inv_scale))
+      return fail(RMSMP_EINVAL, "out_kind 3 needs a positive, finite out_inv_scale");
+    if (ep->out_zero_point < 0 || ep->out_zero_point > 15) return fail(RMSMP_EINVAL, "out_zero_point must be in 0..15");
+  }
   if (ep->relu != 0 && ep->relu != 1) return fail(RMSMP_EINVAL, "relu must be 0 or 1");
   if (ep->act_bits == 4 && (ep->act_zero_point < 0 || ep->act_zero_point > 15))
     return fail(RMSMP_EINVAL, "act_zero_point must be in 0..15 for 4-bit codes");
   if (ep->act_bits == 8 && (ep->act_zero_point < -128 || ep->act_zero_point > 127))
     return fail(RMSMP_EINVAL, "act_zero_point must be in -128..127 for 8-bit codes");
-  if (ep->out_kind == 2 && (M & 1)) return fail(RMSMP_ESHAPE, "4-bit output needs an even number of rows");
+  if (ep->out_kind >= 2 && (M & 1)) return fail(RMSMP_ESHAPE, "4-bit output needs an even number of rows");
   return RMSMP_OK;
+}
+
+// Break points of the GELU epilogue for the scale and zero point of this call; the last pair a
+// thread asked for is kept, so a serving loop with fixed scales pays for the bisection once.
+void fill_gelu_table(const rmsmp_epilogue& ep, rmsmp::GemmArgs* a) {
+  if (ep.out_kind != 3) return;
+  thread_local float cached_inv = 0.0f;
+  thread_local int32_t cached_z = -1;
+  thread_local rmsmp::GeluTable cached;
+  if (cached_inv != ep.out_inv_scale || cached_z != ep.out_zero_point) {
+    rmsmp::gelu_table(ep.out_inv_scale, ep.out_zero_point, &cached);
+    cached_inv = ep.out_inv_scale;
+    cached_z = ep.out_zero_point;
+  }
+  a->gelu = cached;
 }
 
 }  // namespace
@@ -228,6 +250,7 @@ rmsmp_status rmsmp_gemm(const rmsmp_packed* Wp, const void* X, int64_t N, const 
   a.Y = Y;
   a.ep = *ep;
   a.conv = 0;
+  fill_gelu_table(*ep, &a);
   hipError_t e = (hipError_t)rmsmp::launch_gemm(a, stream);
   if (e != hipSuccess) return hip_fail(e, "gemm: kernel launch");
   return RMSMP_OK;
@@ -279,6 +302,21 @@ rmsmp_status rmsmp_debug_last_dispatch(int32_t out[5]) {
   return RMSMP_OK;
 }
 
+rmsmp_status rmsmp_debug_gelu_breakpoints(float out_inv_scale, int32_t out_zero_point, float rise[16], float fall[16],
+                                          float* y_split, int32_t* fall_base, int32_t* n_fall) {
+  if (!rise || !fall || !y_split || !fall_base || !n_fall) return fail(RMSMP_EINVAL, "debug_gelu_breakpoints: NULL output");
+  if (!(out_inv_scale > 0.0f) || !std::isfinite(out_inv_scale) || out_zero_point < 0 || out_zero_point > 15)
+    return fail(RMSMP_EINVAL, "debug_gelu_breakpoints: scale must be positive and finite, zero point in 0..15");
+  rmsmp::GeluTable t;
+  rmsmp::gelu_table(out_inv_scale, out_zero_point, &t);
+  std::memcpy(rise, t.rise, sizeof(t.rise));
+  std::memcpy(fall, t.fall, sizeof(t.fall));
+  *y_split = t.y_split;
+  *fall_base = t.fall_base;
+  *n_fall = t.n_fall;
+  return RMSMP_OK;
+}
+
 rmsmp_status rmsmp_debug_measure_peaks(double* mfma_int8_tops, double* copy_gbs) {
   hipError_t e = (hipError_t)rmsmp::measure_peaks(mfma_int8_tops, copy_gbs);
   if (e != hipSuccess) return hip_fail(e, "debug_measure_peaks");
@@ -323,6 +361,7 @@ rmsmp_status rmsmp_conv2d(const rmsmp_packed* Wp, const void* X, const rmsmp_con
   a.d = *d;
   a.OH = OH;
   a.OW = OW;
+  fill_gelu_table(*ep, &a);
   if (conv_is_implicit(Wp, d, ep->act_bits)) {
     a.K = Wp->host.K;
     a.X = X;

@@ -294,7 +294,7 @@ __global__ __launch_bounds__(256, 3) void conv_first_kernel(GemmArgs a, FirstGeo
             rm.base = (const int*)__builtin_assume_aligned(meta + mt * (4 * TILE_M) + 16 * hh, 64);
             rm.rows = TILE_M;
             const int64_t ncol[1] = {n};
-            finish_tiles<1>(ea, tr.kind, acc, rm, n_rows, ncol);
+            finish_tiles<1, RowMetaLds, false>(ea, tr.kind, acc, rm, n_rows, ncol);  // (no GELU epilogue here)
           } else {
             uint32_t packed[2];
             float brow[16];
@@ -371,6 +371,7 @@ static uint32_t cf_div_magic(int64_t d) {
 
 static bool conv_first_applies(const GemmArgs& a) {
   if (!(a.conv && a.w.k_layout == K_FILTER_ROWS && a.ep.act_bits == 8)) return false;
+  if (a.ep.out_kind == 3) return false;  // the GELU epilogue lives in the general kernels
   if (a.d.C != 3 || a.d.stride != 2 || a.d.KH != a.d.KW) return false;
   if (!(a.d.KH == 3 || a.d.KH == 5 || a.d.KH == 7)) return false;
   if (!(a.d.pad == 1 || a.d.pad == 3)) return false;  // pixel pairs start on an odd pixel, at most 4 left of the image

@@ -142,7 +142,7 @@ struct EpArgs {
   const float* bias;
   int64_t N, M;
   float act_scale, out_inv_scale;
-  int zp, relu, out_kind;
+  int zp, relu, out_kind, out_zero_point;
 };
 
 __device__ __forceinline__ EpArgs pin_epilogue_args(const GemmArgs& a) {
@@ -156,9 +156,10 @@ __device__ __forceinline__ EpArgs pin_epilogue_args(const GemmArgs& a) {
   e.zp = a.ep.act_zero_point;
   e.relu = a.ep.relu;
   e.out_kind = a.ep.out_kind;
+  e.out_zero_point = a.ep.out_zero_point;
   // an empty asm that "modifies" the values keeps the loads here
   asm volatile("" : "+s"(e.Y), "+s"(e.bias), "+s"(e.N), "+s"(e.M), "+s"(e.act_scale), "+s"(e.out_inv_scale), "+s"(e.zp),
-               "+s"(e.relu), "+s"(e.out_kind));
+               "+s"(e.relu), "+s"(e.out_kind), "+s"(e.out_zero_point));
   return e;
 }
 
@@ -218,6 +219,61 @@ __device__ __forceinline__ void requant_block(const v16i& v, const float (&m)[16
   }
 }
 
+// GELU + affine 4-bit code of one pixel block (out_kind 3): g = y * Phi(y) in float64 rounded to
+// fp32, code = clamp(rint(g * inv_s) + z, 0, 15).  As a function of the fp32 pre-activation y the
+// code is piecewise constant, and the host has found its break points exactly (GeluTable, handed
+// over inside the kernel arguments): for y at or above the minimum of GELU the code is the largest
+// c with rise[c] <= y, searched downwards from the code y itself would get (never too low, since
+// GELU(y) <= max(y, 0)); below the minimum it is fall_base plus the number of fall[j] >= y.
+// The kernel arguments start with the GemmArgs block in every kernel of the library.
+__device__ __forceinline__ void gelu_requant_block(const v16i& v, const float (&m)[16], const float (&bias)[16], float inv_s,
+                                                   int z_out, uint32_t (&packed)[2]) {
+  // (the table is read in place: scalar loads for the wave-uniform fields, a per-lane load for rise[code])
+  typedef const __attribute__((address_space(4))) char karg_char;
+  typedef const __attribute__((address_space(4))) GeluTable karg_table;
+  karg_table* const tab = (karg_table*)((karg_char*)__builtin_amdgcn_kernarg_segment_ptr() + __builtin_offsetof(GemmArgs, gelu));
+  const float y_split = tab->y_split;
+  const int fix_steps = tab->fix_steps, fall_base = tab->fall_base, n_fall = tab->n_fall;
+  const RMSMP_GLOBAL float* const rise = (const RMSMP_GLOBAL float*)(uintptr_t)tab->rise;
+  int code[16];
+  float y[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    y[r] = __fadd_rn(__fmul_rn((float)v[r], m[r]), bias[r]);
+    const float t = fminf(__fmul_rn(fmaxf(y[r], 0.0f), inv_s), 15.0f);
+    const int c = (int)__builtin_rintf(t) + z_out;
+    code[r] = c < 15 ? c : 15;
+  }
+#pragma unroll 1
+  for (int s = 0; s < fix_steps; ++s) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) code[r] -= (y[r] < rise[code[r]]) ? 1 : 0;
+  }
+  if (n_fall > 0) {
+    int cf[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) cf[r] = fall_base;
+#pragma unroll 1
+    for (int j = 0; j < n_fall; ++j) {
+      const float f = tab->fall[j];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) cf[r] += (y[r] <= f) ? 1 : 0;
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) code[r] = y[r] < y_split ? cf[r] : code[r];
+  } else {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) code[r] = y[r] < y_split ? fall_base : code[r];
+  }
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    uint32_t w = 0u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w |= (uint32_t)code[8 * h + i] << (4 * i);
+    packed[h] = w;
+  }
+}
+
 // Finish NB 32x32 accumulator tiles of the same weight tile (NB pixel blocks): zero-point
 // correction, per-row scale, bias, ReLU, then int32 / fp32 / nibble-packed 4-bit store.
 // Register r of lane l is grouped row 16*(l/32)+r of the weight tile and column n[j]; the 16
@@ -230,7 +286,8 @@ __device__ __forceinline__ void requant_block(const v16i& v, const float (&m)[16
 // them (an exact shift); the float paths fold the factor into the per-row multiplier instead:
 // float(16 a) * (m / 16) and float(a) * m are the same float, because scaling by a power of two
 // commutes with rounding.
-template <int NB, class Meta>
+// GELU: whether the calling kernel carries the GELU epilogue (out_kind 3) at all.
+template <int NB, class Meta, bool GELU = true>
 __device__ __forceinline__ void finish_tiles(const EpArgs& a, int kind, const v16i (&acc)[NB], const Meta& rm,
                                              int n_rows, const int64_t (&n)[NB]) {
   if (n_rows <= 0) return;
@@ -292,6 +349,10 @@ __device__ __forceinline__ void finish_tiles(const EpArgs& a, int kind, const v1
   // rounds to a non-positive value), so the separate maximum is skipped
   const bool relu_q = relu && !(a.out_inv_scale > 0.0f);
   uint32_t packed[NB][2];
+  if (GELU && out_kind == 3) {
+#pragma unroll
+    for (int j = 0; j < NB; ++j) gelu_requant_block(v[j], m, bias, a.out_inv_scale, a.out_zero_point, packed[j]);
+  } else {
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
     if (has_bias) {
@@ -305,6 +366,7 @@ __device__ __forceinline__ void finish_tiles(const EpArgs& a, int kind, const v1
       else
         requant_block<false, false>(v[j], m, bias, a.out_inv_scale, packed[j]);
     }
+  }
   }
 #pragma unroll
   for (int j = 0; j < NB; ++j) {

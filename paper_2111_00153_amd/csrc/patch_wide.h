@@ -47,6 +47,7 @@ constexpr int PW_PATCH_UNROLL = 6;  // 16-byte patch pieces in flight per thread
 // x 8 pieces, 512 + halo x 2, ...), those of the 1x1 layers / GEMMs exactly six (64 x 24): a batch
 // of five is one read, one decode and four registers less for the former.
 constexpr int pw_batch(int taps) { return taps == 9 ? 5 : PW_PATCH_UNROLL; }
+constexpr bool wide_has_gelu(int taps, int xb) { return taps == 1 && xb == 2; }
 // Row metadata of a tile pair in LDS, field by field [field][64 rows]: rowscale bits, rowsum, original
 // row, grouped position, and two values formed once per work-group for the lean 4-bit epilogue: the
 // row's multiplier rowscale * activation scale (* 1/16 for shift-decoded tiles) and zero point * rowsum
@@ -160,6 +161,10 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
   // the benchmarked layer and is not instantiated)
   constexpr int NW = KS * NWT * MS;
   static_assert(NW == 4 || NW == 8, "four or eight waves");
+  // The GELU epilogue (out_kind 3) exists where a transformer's feed-forward layer lands and the
+  // register budget has room for it: plain GEMMs / 1x1 layers at 64 pixels per wave.  The host
+  // sends such a layer nowhere else.
+  constexpr bool WIDE_GELU = wide_has_gelu(TAPS, XB);
   constexpr int NT = LANES * NW;
   static_assert(XB == 2 || XB == 4, "32-pixel blocks per wave");
   constexpr int PW_XB = XB;
@@ -587,7 +592,7 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
         ncol[o] = col0 + 32 * (c0 + o);
         blocks[o] = mine[ti * BPT + c0 + o];
       }
-      finish_tiles<CH>(ea, kind, blocks, rm, n_rows, ncol);
+      finish_tiles<CH, RowMetaLds, WIDE_GELU>(ea, kind, blocks, rm, n_rows, ncol);
     }
   }
   RMSMP_PHASE(6);
@@ -686,6 +691,8 @@ inline int launch_wide_tc(const WidePlan& p, hipStream_t s) {
   if (p.xb == 2 && p.ks == 4 && p.nwt == 1 && p.ms == 1) return launch_wide_t<TAPS, CPT, 2, 4, 1, 1, DEEP>(p, s);
   if (p.xb == 2 && p.ks == 1 && p.nwt == 1 && p.ms == 4) return launch_wide_t<TAPS, CPT, 2, 1, 1, 4, DEEP>(p, s);
   if (p.xb == 2 && p.ks == 1 && p.nwt == 4 && p.ms == 1) return launch_wide_t<TAPS, CPT, 2, 1, 4, 1, DEEP>(p, s);
+  if (p.xb == 4 && p.ks == 2 && p.nwt == 1 && p.ms == 2) return launch_wide_t<TAPS, CPT, 4, 2, 1, 2, DEEP>(p, s);
+  if (p.xb == 2 && p.ks == 2 && p.nwt == 1 && p.ms == 2) return launch_wide_t<TAPS, CPT, 2, 2, 1, 2, DEEP>(p, s);
   return (int)hipErrorInvalidValue;
 }
 

@@ -29,11 +29,13 @@ static uint32_t wide_div_magic(int64_t d) {
 // One candidate split of the four waves; fills the plan when the layer fits it.
 // cc: channels staged at a time (all of them, or a part of a deep 1x1 layer / GEMM).
 static bool wide_plan_mode(const GemmArgs& a, int cc, int xb, int ks, int nwt, int ms, WidePlan* plan) {
-  const bool known = (xb == 4 && ((ks == 4 && nwt == 1 && ms == 1) || (ks == 2 && nwt == 2 && ms == 1) ||
+  const bool known = (ks == 2 && nwt == 1 && ms == 2 && (xb == 2 || xb == 4)) ||
+                     (xb == 4 && ((ks == 4 && nwt == 1 && ms == 1) || (ks == 2 && nwt == 2 && ms == 1) ||
                                  (ks == 1 && nwt == 4 && ms == 1) || (ks == 1 && nwt == 1 && ms == 4))) ||
                      (xb == 2 && ((ks == 2 && nwt == 2 && ms == 1) || (ks == 4 && nwt == 1 && ms == 1) ||
                                  (ks == 1 && nwt == 1 && ms == 4) || (ks == 1 && nwt == 4 && ms == 1)));
   if (!known) return false;
+  if (a.ep.out_kind == 3 && !wide_has_gelu(a.d.KH * a.d.KW, xb)) return false;
   const int cpt = cc / KSTEP;
   if (cpt % ks != 0 || a.d.KH * a.d.KW * (cpt / ks) < 2) return false;
   const int64_t S = a.d.stride;
@@ -125,13 +127,14 @@ static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
   if (row_extra < 0 || row_extra + img_extra < 0) return false;
   const int n_pairs = (a.w.n_tiles + 1) / 2;
   // How the four waves are shared out: the candidate with the lowest estimated time wins.  The
-  // estimate is a per-work-group critical path (cycles, constants fitted to per-phase clock stamps
-  // on an MI355X) times the number of rounds the grid needs: prologue (a fixed part plus the
+  // estimate is a per-work-group critical path (cycles; the constants started from per-phase clock
+  // stamps and were then fitted to the measured launch times of every candidate on the ResNet-18 and
+  // BERT-base layer shapes on an MI355X) times the number of rounds the grid needs: prologue (a fixed part plus the
   // patch's way through LDS), K loop (cycles per MFMA depend on how many MFMAs share a decoded
   // weight fragment), partial-sum exchange (LDS traffic), epilogue (per finished 32x32 block).
   // Work-groups that share a compute unit overlap everything except their K loops' MFMAs.
   struct Mode { int xb, ks, nwt, ms; };
-  const Mode modes[] = {{4, 1, 1, 4}, {4, 1, 4, 1}, {4, 2, 2, 1}, {4, 4, 1, 1}, {2, 2, 2, 1}, {2, 4, 1, 1}, {2, 1, 1, 4}, {2, 1, 4, 1}};
+  const Mode modes[] = {{4, 1, 1, 4}, {4, 1, 4, 1}, {4, 2, 2, 1}, {4, 4, 1, 1}, {4, 2, 1, 2}, {2, 2, 2, 1}, {2, 4, 1, 1}, {2, 1, 1, 4}, {2, 1, 4, 1}, {2, 2, 1, 2}};
   WidePlan best;
   double best_cost = 0;
   bool have = false;
@@ -142,11 +145,11 @@ static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
     const double wgs = (double)p.g.gx * p.g.gy;
     const double steps = (double)taps * cpt * nchunk / m.ks;
     const double mfmas = steps * 2 * m.xb;
-    const double kloop = mfmas * (m.xb == 4 ? 50.0 : 58.0);
+    const double kloop = mfmas * (m.xb == 4 ? 36.3 : 49.7);
     // (every further part of the channels is staged like the first, between two barriers)
-    const double prologue = 1300.0 + (double)p.g.patch_rows * p.g.row_stride / 15.7 + (nchunk - 1) * (1500.0 + (double)p.g.patch_rows * p.g.row_stride / 15.7);
-    const double exchange = m.ks == 1 ? 0.0 : 400.0 + (double)pw_xch_bytes(m.xb, m.ks, m.ks * m.nwt * m.ms) / 45.0;
-    const double epilogue = 1800.0 + 670.0 * (2.0 * m.xb / m.ks);
+    const double prologue = 818.0 + (double)p.g.patch_rows * p.g.row_stride / 17.6 + (nchunk - 1) * (1500.0 + (double)p.g.patch_rows * p.g.row_stride / 17.6);
+    const double exchange = m.ks == 1 ? 0.0 : (double)pw_xch_bytes(m.xb, m.ks, m.ks * m.nwt * m.ms) / 26.3;
+    const double epilogue = 1520.0 + 665.0 * (2.0 * m.xb / m.ks);
     const double t_wg = prologue + kloop + exchange + epilogue;
     const int by_lds = (int)((160 * 1024) / p.lds), by_regs = (m.xb == 4 || nchunk > 1) ? 2 : 3;
     const int k_max = by_lds < by_regs ? by_lds : by_regs;
@@ -154,7 +157,7 @@ static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
     // what one more work-group on the same compute unit adds: its MFMAs (the matrix pipe is
     // shared) and about a third of everything else; with 64 pixels per wave the vector ALU is the
     // shared bottleneck throughout, and little of the rest overlaps
-    const double extra = m.xb == 4 ? mfmas * 36.0 + 0.35 * (t_wg - kloop) : mfmas * 52.0 + 0.7 * (t_wg - kloop);
+    const double extra = m.xb == 4 ? mfmas * 28.5 + 0.264 * (t_wg - kloop) : mfmas * 46.7 + 0.434 * (t_wg - kloop);
     // the busiest compute units get n work-groups (a few stragglers beyond a whole number do not
     // count): whole rounds of k_max sharing the unit, then the rest
     const int n = per_cu < 1.0 ? 1 : (int)ceil(per_cu - 0.15);

@@ -108,6 +108,18 @@ struct TileRef {
   int64_t blob_off;
 };
 
+// Break points of the GELU + affine 4-bit code as a function of the fp32 pre-activation y
+// (gelu_host.cpp).  Rising branch (y >= y_split): code = max{ c : rise[c] <= y }; the kernels start
+// from the code y itself would get, which is never below and at most fix_steps above.  Falling
+// branch (y < y_split): code = fall_base + #{ j < n_fall : y <= fall[j] }.
+struct GeluTable {
+  float rise[16];
+  float fall[16];
+  float y_split;
+  int32_t fix_steps, fall_base, n_fall;
+};
+void gelu_table(float inv_s, int32_t zero_point, GeluTable* t);
+
 struct GemmArgs {
   DevicePacked w;
   int64_t M = 0, K = 0, N = 0;
@@ -118,6 +130,8 @@ struct GemmArgs {
   int32_t conv = 0;
   rmsmp_conv_desc d{};
   int32_t OH = 0, OW = 0;
+  // out_kind 3 only; kept last so that the other epilogues never fetch it
+  GeluTable gelu{};
 };
 
 struct Im2colArgs {

@@ -217,3 +217,101 @@ def test_remaining_inference_gemms(rm, oracle, name, M, K, N, ratio, bits):
     assert np.all(np.abs(Yf.cpu().numpy() - y) <= 1e-5 * np.abs(y))
     assert np.array_equal(_grouped_to_rows(rm, Yq.cpu().numpy(), p.perm), q)
     p.free()
+
+
+# ---- GELU epilogue of the feed-forward up-projection (out_kind 3)
+
+@pytest.mark.parametrize("M,K,N,inv_s,z_out,with_bias", [
+    (3072, 768, 4096, 2.0, 1, True),      # configs[2]'s shape: the LDS-resident kernel
+    (3072, 768, 4096, 6.5, 2, False),     # a finer output scale: codes below the zero point on GELU's negative lobe
+    (130, 576, 300, 6.0, 0, True),        # general kernel, ragged tiles
+    (96, 1024, 8, 5.0, 1, True),          # skinny kernel
+])
+def test_gelu_epilogue_matches_oracle(rm, oracle, M, K, N, inv_s, z_out, with_bias):
+    """BERT-base FFN up-projection with the GELU + affine 4-bit requantization fused: every 4-bit code
+    against the oracle (GELU in float64 from the same fp32 pre-activation)."""
+    rng = si.rng_for(2, M + N)
+    W = si.weights_bert(rng, M, K)
+    scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, 35, 60, 5))
+    xq, s_x, z = si.affine_u4_from_float(rng.standard_normal((N, K)))
+    bias = rng.normal(0.0, 0.4, M).astype(np.float32) if with_bias else None
+    p = rm.rmsmp_pack_weights(W, scheme)
+    ref = oracle.quantize_rows(W, scheme, want_levels=False)
+    acc = oracle.gemm_acc(ref["wint"], xq.astype(np.int32))
+    inv = float(np.float32(inv_s))
+    _, q = oracle.epilogue_gelu(acc, oracle.rowsum(ref["wint"]), z, ref["rowscale"], s_x, bias, inv, z_out)
+    assert len(np.unique(q)) >= 8, np.unique(q)  # the case spans the code range
+    X = _dev(rm.pack_u4(xq))
+    bias_d = None if bias is None else _dev(bias)
+    Yq = torch.full((N, M // 2), 0xEE, dtype=torch.uint8, device=DEV)
+    rm.rmsmp_gemm(p, X, N, rm.make_epilogue(s_x, z, 4, bias_d, False, rm.OUT_GELU_U4, inv, z_out), Yq)
+    torch.cuda.synchronize()
+    assert np.array_equal(_grouped_to_rows(rm, Yq.cpu().numpy(), p.perm), q)
+    p.free()
+
+
+def test_gelu_epilogue_conv_and_argument_errors(rm, oracle):
+    """The same epilogue behind rmsmp_conv2d (1x1 and 3x3), and the argument checks of out_kind 3."""
+    rng = np.random.default_rng(77)
+    for (B, C, H, k, s, pad, M) in ((2, 64, 12, 3, 1, 1, 96), (3, 128, 9, 1, 1, 0, 160)):
+        K = C * k * k
+        W = si.weights_bert(rng, M, K)
+        scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, 35, 60, 5))
+        x = si.act_codes_u4(rng, (B, H, H, C))
+        bias = rng.normal(0.0, 0.3, M).astype(np.float32)
+        p = rm.rmsmp_pack_weights(W, scheme, taps=k * k)
+        d = rm.ConvDesc(B, C, H, H, k, k, s, pad)
+        od = oracle.conv_desc(B, C, H, H, k, k, s, pad)
+        ref = oracle.quantize_rows(W, scheme, want_levels=False)
+        acc = oracle.conv_acc(ref["wint"].reshape(M, C, k, k), x.astype(np.int32), od, zpad=7)
+        _, q = oracle.epilogue_gelu(acc, oracle.rowsum(ref["wint"]), 7, ref["rowscale"], 0.02, bias, 2.5, 1)
+        N = acc.shape[1]
+        Yq = torch.full((N, M // 2), 0xEE, dtype=torch.uint8, device=DEV)
+        rm.rmsmp_conv2d(p, _dev(rm.pack_u4(x)), d, rm.make_epilogue(0.02, 7, 4, _dev(bias), False, rm.OUT_GELU_U4, 2.5, 1), Yq)
+        torch.cuda.synchronize()
+        assert np.array_equal(_grouped_to_rows(rm, Yq.cpu().numpy(), p.perm), q)
+        for bad in (rm.make_epilogue(0.02, 7, 4, None, True, rm.OUT_GELU_U4, 2.5, 1),      # relu with GELU
+                    rm.make_epilogue(0.02, 7, 4, None, False, rm.OUT_GELU_U4, 0.0, 1),     # no scale
+                    rm.make_epilogue(0.02, 7, 4, None, False, rm.OUT_GELU_U4, 2.5, 16)):   # zero point out of range
+            with pytest.raises(rm.RmsmpError) as e:
+                rm.rmsmp_conv2d(p, _dev(rm.pack_u4(x)), d, bad, Yq)
+            assert e.value.code == 1
+        p.free()
+
+
+def test_variance_assigned_layer_matches_oracle(rm, oracle):
+    """A configs[3] layer (layer3.1.conv1's geometry, batch 2) whose PoT-4 / Fixed-4 rows are chosen by
+    weight variance (Alg. 1, else-branch) instead of the seeded permutation: the library's assignment equals
+    the oracle's, and the layer computed from it matches the oracle in every accumulator and 4-bit code."""
+    name, C, M, k, s, pad, H = si.RESNET18_CONVS[13]
+    B = 2
+    rng = si.rng_for(3, 13)
+    W = si.weights_rowscaled(rng, M, C * k * k)
+    counts = rm.rmsmp_ratio_counts(M, 35, 60, 5)
+    seeded = si.scheme_permutation(rng, counts)
+    start = np.where(seeded == si.FIXED8, si.FIXED8, si.FIXED4).astype(np.uint8)
+    scheme = rm.rmsmp_assign_by_variance(W, start, counts[1])
+    assert np.array_equal(scheme, oracle.assign_by_variance(W, start, counts[1]))
+    assert tuple(np.bincount(scheme, minlength=3)) == tuple(counts)
+    var = W.astype(np.float64).var(axis=1)
+    assert var[scheme == si.POT4].max() <= var[scheme == si.FIXED4].min()
+    x = si.act_codes_u4(rng, (B, H, H, C))
+    p = rm.rmsmp_pack_weights(W, scheme, taps=k * k)
+    d = rm.ConvDesc(B, C, H, H, k, k, s, pad)
+    od = oracle.conv_desc(B, C, H, H, k, k, s, pad)
+    ref = oracle.quantize_rows(W, scheme, want_levels=False)
+    acc = oracle.conv_acc(ref["wint"].reshape(M, C, k, k), x.astype(np.int32), od, 0)
+    rs = oracle.rowsum(ref["wint"])
+    _, y, _ = oracle.epilogue(acc, rs, 0, ref["rowscale"], 0.05, None, True)
+    inv = np.float32(15.0 / float(np.percentile(y, 99.9)))
+    _, _, q = oracle.epilogue(acc, rs, 0, ref["rowscale"], 0.05, None, True, inv)
+    N = acc.shape[1]
+    X = _dev(rm.pack_u4(x))
+    Yi = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    rm.rmsmp_conv2d(p, X, d, rm.make_epilogue(0.05, 0, 4, None, False, rm.OUT_INT32), Yi)
+    Yq = torch.empty((N, M // 2), dtype=torch.uint8, device=DEV)
+    rm.rmsmp_conv2d(p, X, d, rm.make_epilogue(0.05, 0, 4, None, True, rm.OUT_U4, inv), Yq)
+    torch.cuda.synchronize()
+    assert np.array_equal(Yi.cpu().numpy(), acc)
+    assert np.array_equal(_grouped_to_rows(rm, Yq.cpu().numpy(), p.perm), q)
+    p.free()
