@@ -231,6 +231,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle (its timing and the in-run check)")
     ap.add_argument("--no-extras", action="store_true", help="skip the other configurations and the machine peaks")
+    ap.add_argument("--layer-iters", type=int, default=200, help="launches per layer in the per-layer timing pass")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (a known-size kernel to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE readings with)")
@@ -293,7 +294,7 @@ def main():
         L["kernel"] = kernel_of(rm, L)
     torch.cuda.synchronize()
     for L in layers:
-        us = time_block(torch, [L["launch"]], 200, 10)
+        us = time_block(torch, [L["launch"]], args.layer_iters, 10)
         L["us"] = us
         per_layer[L["name"]] = dict(us=round(us, 3), tops=round(L["ops"] / us / 1e6, 1), kernel=L["kernel"])
         fam = families.setdefault(L["kernel"], dict(us=0.0, ops=0.0, launches=0))
@@ -305,7 +306,7 @@ def main():
     dom_name = max(families, key=lambda k: families[k]["us"])
     dom_layers = [L for L in layers if L["kernel"] == dom_name]
     # the dominant kernel's average launch duration: its layers round-robin, back to back, between two events
-    dom_us = time_block(torch, [L["launch"] for L in dom_layers], 100 * len(dom_layers), 4 * len(dom_layers))
+    dom_us = time_block(torch, [L["launch"] for L in dom_layers], max(1, args.layer_iters // 2) * len(dom_layers), 4 * len(dom_layers))
     dom_ops = sum(L["ops"] for L in dom_layers) / len(dom_layers)
     achieved = dom_ops / dom_us / 1e6
 

@@ -186,9 +186,21 @@ static int launch_general(const GemmArgs& a, hipStream_t s) {
 constexpr int SK_THREADS = 512;
 constexpr int SK_WAVES = 8;
 constexpr int SK_CHUNK = 16;  // K steps whose loads are in flight together per wave
+#ifdef RMSMP_SKINNY_STAMPS  // tuning builds: per-wave clock stamps of the skinny kernel's phases
+__device__ unsigned long long* g_sk_buf = nullptr;
+#define SK_STAMP(i) do { __builtin_amdgcn_sched_barrier(0); sk_t[i] = clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
+#define SK_FLUSH() do { if (g_sk_buf && (threadIdx.x & 63) == 0) for (int i_ = 0; i_ < 8; ++i_) g_sk_buf[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 8 + i_] = sk_t[i_]; } while (0)
+#else
+#define SK_STAMP(i) do { } while (0)
+#define SK_FLUSH() do { } while (0)
+#endif
 
 template <int KIND, int NB>
 __device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, const TileRef& tr, int mt) {
+#ifdef RMSMP_SKINNY_STAMPS
+  unsigned long long sk_t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
+  SK_STAMP(0);
   const EpArgs ea = pin_epilogue_args(a);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -215,7 +227,10 @@ __device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, co
 
 #pragma unroll 1
   for (int c0 = 0; c0 < S; c0 += SK_CHUNK) {
-    // all weight fragments of the chunk first ...
+    // All weight fragments of the chunk first -- they come from memory and their addresses need next
+    // to no arithmetic, and the code that runs once at the start of a kernel runs at the speed of
+    // instruction fetch, so every instruction in front of these reads delays them -- then this
+    // wave's slice of the activations (ROWS rows x SK_CHUNK*16 packed bytes, a few KB from the cache).
     typename RawFrag<KIND>::type raw[SK_CHUNK];
 #pragma unroll
     for (int u = 0; u < SK_CHUNK; ++u) {
@@ -223,22 +238,30 @@ __device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, co
       ks = ks < nks ? ks : nks - 1;
       raw[u] = load_raw<KIND>(wbase + (int64_t)ks * (LANES * FRAG), wl);
     }
-    // ... then this wave's slice of the activations: ROWS rows x (SK_CHUNK*16) packed bytes
+    constexpr int XI = ROWS * SK_CHUNK / LANES;
+    uint4 xw[XI];
     {
       const int64_t col0 = (int64_t)(ks0 + c0) * 16;  // byte offset inside an activation row
 #pragma unroll
-      for (int i = 0; i < ROWS * SK_CHUNK / LANES; ++i) {
+      for (int i = 0; i < XI; ++i) {
         const int pidx = i * LANES + lane;
         const int row = pidx / SK_CHUNK, piece = pidx % SK_CHUNK;
         const int64_t n = row < (int)a.N ? row : (int)a.N - 1;  // rows past N repeat the last one; never stored
         int64_t cb = col0 + piece * 16;
         cb = cb + 16 <= ldx ? cb : ldx - 16;  // past the end of K: any data, its weights are zero
-        const uint4 w = *(const uint4*)(X + n * ldx + cb);
-        *(uint2*)(xs + row * x_stride + piece * 16) = make_uint2(w.x, w.y);
-        *(uint2*)(xs + row * x_stride + piece * 16 + 8) = make_uint2(w.z, w.w);
+        xw[i] = *(const uint4*)(X + n * ldx + cb);
       }
     }
+    SK_STAMP(1);
+#pragma unroll
+    for (int i = 0; i < XI; ++i) {
+      const int pidx = i * LANES + lane;
+      const int row = pidx / SK_CHUNK, piece = pidx % SK_CHUNK;
+      *(uint2*)(xs + row * x_stride + piece * 16) = make_uint2(xw[i].x, xw[i].y);
+      *(uint2*)(xs + row * x_stride + piece * 16 + 8) = make_uint2(xw[i].z, xw[i].w);
+    }
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave's LDS writes have landed (region is private)
+    SK_STAMP(2);
 #pragma unroll
     for (int u = 0; u < SK_CHUNK; ++u) {
       const int ks = ks0 + c0 + u;
@@ -253,8 +276,16 @@ __device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, co
     }
   }
 
+  SK_STAMP(3);
+  // The waves that finish a pixel block fetch their row metadata now, behind the barrier and the
+  // reduction: at the end it would be one more memory round trip in front of the stores.  (Not
+  // earlier: a load under a wave-dependent branch makes the compiler drain every outstanding load
+  // where the branches join, and up there that would be in front of the weight reads.)
+  RowMeta rm;
+  if (wave < NB) load_row_meta(a.w, mt, lane, rm);
   // ---- add the eight partial sums: wave j (< NB) finishes pixel block j
   __syncthreads();
+  SK_STAMP(4);
   {
     int* dst = (int*)smem + wave * (NB * 16 * LANES);
 #pragma unroll
@@ -265,11 +296,16 @@ __device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, co
             (v4i){acc[j][4 * q], acc[j][4 * q + 1], acc[j][4 * q + 2], acc[j][4 * q + 3]};
   }
   __syncthreads();
-  if (wave >= NB) return;
+  SK_STAMP(5);
+  if (wave >= NB) {
+    SK_FLUSH();
+    return;
+  }
   v16i sum[1];
 #pragma unroll
   for (int r = 0; r < 16; ++r) sum[0][r] = 0;
-#pragma unroll 1
+  // (four waves' parts in flight at a time: read one after the other, the eight LDS round trips add up)
+#pragma unroll 4
   for (int w = 0; w < SK_WAVES; ++w) {
     const int* src = (const int*)smem + w * (NB * 16 * LANES) + wave * (16 * LANES);
 #pragma unroll
@@ -281,15 +317,21 @@ __device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, co
       sum[0][4 * q + 3] += got.w;
     }
   }
-  RowMeta rm;
-  load_row_meta(a.w, mt, lane, rm);
+  SK_STAMP(6);
   const int64_t ncol[1] = {32 * wave + (lane & 31)};
   finish_tiles<1>(ea, KIND, sum, rm, lane_rows(tr.nvalid, lane), ncol);
+  SK_STAMP(7);
+  SK_FLUSH();
 }
 
 template <int NB>
 __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+  // Every kernel argument the kernel will read, asked for here: left to itself the compiler fetches
+  // an argument where it is first used, which puts half a dozen dependent scalar-memory round trips
+  // in front of the first weight read; this way they are one.
+  asm volatile("" ::"s"(a.w.blob), "s"(a.w.p_meta), "s"(a.w.p_lut), "s"(a.w.nks), "s"(a.w.class_tiles[0]), "s"(a.w.class_tiles[1]),
+               "s"(a.w.class_rows[0]), "s"(a.w.class_rows[1]), "s"(a.w.class_rows[2]), "s"(a.K), "s"(a.N), "s"(a.X));
   const int mt = blockIdx.x;
   const TileRef tr = tile_ref(a.w, mt);
   if (tr.kind == TILE_NIB_SHIFT)
