@@ -1,7 +1,10 @@
 #!/usr/bin/env python3
 """Times the library on every benchmark configuration (synthetic inputs, one GPU) and prints a table.
 
-    python -m paper_2111_00153_amd.bench_configs [gemm] [conv] [skinny] [sweep] [extra] [qat]
+    python -m paper_2111_00153_amd.bench_configs [gemm] [conv] [skinny] [sweep] [extra] [qat] [calib]
+
+(`calib` adds one plain 256 MiB device-to-device copy: a kernel of known size to scale rocprofv3's
+FETCH_SIZE / WRITE_SIZE readings with when the script runs under the profiler.)
 
 Protocol: 20 warm-up launches, then five blocks of back-to-back launches on one stream between two
 events; the median block is reported.  Throughput counts 2*M*K*N operations of the logical GEMM
@@ -175,6 +178,12 @@ def main():
         extra_layers()
     if "qat" in which:
         qat_kernels()
+    if "calib" in which:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=DEV).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
 
 
 if __name__ == "__main__":
