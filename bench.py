@@ -8,7 +8,7 @@ Fixed4:PoT4:Fixed8 = 60:35:5 and unsigned 4-bit activations resident in HBM, fus
 requantization -- launched back to back on one stream.  Prints one JSON line.
 
 Besides the contract fields the line carries: per-layer times, the time share of every kernel
-family, the other configurations (configs[1], configs[2], configs[4] with cold weights), the
+family, the same step with the batch cut in two halves on two streams, the other configurations (configs[1], configs[2], configs[4] with cold weights), the
 measured MFMA-only and stream-copy rates of this machine, and the CPU oracle's rate.
 """
 import argparse
@@ -208,6 +208,50 @@ def other_configs(rm, si, torch, dev):
     return out
 
 
+def two_stream_schedule(rm, torch, layers, steps, warm):
+    """The same step with the batch cut in two halves that run on two streams (every image still
+    passes through the layers in order; 40 launches per step).  Launches of the two streams overlap
+    on the chip: one half's prologues, epilogues and launch gaps run under the other half's MFMA
+    phases.  The outputs land in the same buffers and are compared byte for byte with what the
+    one-stream step left there."""
+    half = BATCH // 2
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    expect = [L["Y"].clone() for L in layers]
+    for L in layers:
+        L["Y"].zero_()
+    launchers = []
+    for L in layers:
+        if L["ws"] is not None:
+            raise SystemExit("bench.py: a layer with an im2col workspace cannot be shared by two streams")
+        d = rm.ConvDesc(half, L["C"], L["H"], L["H"], L["k"], L["k"], L["s"], L["pad"])
+        n = L["N"] // 2
+        launchers.append([rm.conv2d_launcher(L["p"], L["X"][i * half:(i + 1) * half], d, L["ep"], L["Y"][i * n:(i + 1) * n],
+                                             L["ws"], stream=streams[i]) for i in range(2)])
+    torch.cuda.synchronize()
+
+    def step():
+        for pair in launchers:
+            pair[0]()
+            pair[1]()
+
+    for _ in range(warm):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    same = all(bool(torch.equal(L["Y"], e)) for L, e in zip(layers, expect))
+    if not same:
+        raise SystemExit("bench.py: the two-stream schedule's outputs differ from the one-stream step's")
+    ops = sum(L["ops"] for L in layers)
+    return {"ms_per_step": round(ms, 6), "tops": round(ops / (ms * 1e-3) / 1e12, 2), "launches_per_step": 2 * len(layers),
+            "outputs_identical_to_one_stream_step": same,
+            "note": "batch 64 as two halves of 32 on two streams, layer order kept per image; not the headline "
+                    "(the headline is the one-stream step that the kernel trace and the per-layer times describe)"}
+
+
 def traffic_from_profile(kernel_name):
     """HBM bytes per launch of the dominant kernel as the committed rocprofv3 counter summary of this
     workload states them (a counter cannot be read from inside this script); None when no summary
@@ -329,6 +373,7 @@ def main():
         "cpu_baseline": base,
     }
     if not args.no_extras:
+        out["two_stream_schedule"] = two_stream_schedule(rm, torch, layers, args.steps, args.warmup)
         out["other_configs"] = other_configs(rm, si, torch, dev)
         mfma_tops, copy_gbs = rm.rmsmp_debug_measure_peaks()
         out["measured_peaks"] = {"mfma_only_int8_tops": round(mfma_tops, 1), "stream_copy_gbs": round(copy_gbs, 1),

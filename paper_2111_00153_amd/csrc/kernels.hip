@@ -186,21 +186,11 @@ static int launch_general(const GemmArgs& a, hipStream_t s) {
 constexpr int SK_THREADS = 512;
 constexpr int SK_WAVES = 8;
 constexpr int SK_CHUNK = 16;  // K steps whose loads are in flight together per wave
-#ifdef RMSMP_SKINNY_STAMPS  // tuning builds: per-wave clock stamps of the skinny kernel's phases
-__device__ unsigned long long* g_sk_buf = nullptr;
-#define SK_STAMP(i) do { __builtin_amdgcn_sched_barrier(0); sk_t[i] = clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
-#define SK_FLUSH() do { if (g_sk_buf && (threadIdx.x & 63) == 0) for (int i_ = 0; i_ < 8; ++i_) g_sk_buf[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 8 + i_] = sk_t[i_]; } while (0)
-#else
-#define SK_STAMP(i) do { } while (0)
-#define SK_FLUSH() do { } while (0)
-#endif
 
 template <int KIND, int NB>
 __device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, const TileRef& tr, int mt) {
-#ifdef RMSMP_SKINNY_STAMPS
-  unsigned long long sk_t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#endif
-  SK_STAMP(0);
+  RMSMP_REG_STAMPS_DECLARE();
+  RMSMP_REG_STAMP(0);
   const EpArgs ea = pin_epilogue_args(a);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -252,7 +242,7 @@ __device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, co
         xw[i] = *(const uint4*)(X + n * ldx + cb);
       }
     }
-    SK_STAMP(1);
+    RMSMP_REG_STAMP(1);
 #pragma unroll
     for (int i = 0; i < XI; ++i) {
       const int pidx = i * LANES + lane;
@@ -261,7 +251,7 @@ __device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, co
       *(uint2*)(xs + row * x_stride + piece * 16 + 8) = make_uint2(xw[i].z, xw[i].w);
     }
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave's LDS writes have landed (region is private)
-    SK_STAMP(2);
+    RMSMP_REG_STAMP(2);
 #pragma unroll
     for (int u = 0; u < SK_CHUNK; ++u) {
       const int ks = ks0 + c0 + u;
@@ -276,7 +266,7 @@ __device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, co
     }
   }
 
-  SK_STAMP(3);
+  RMSMP_REG_STAMP(3);
   // The waves that finish a pixel block fetch their row metadata now, behind the barrier and the
   // reduction: at the end it would be one more memory round trip in front of the stores.  (Not
   // earlier: a load under a wave-dependent branch makes the compiler drain every outstanding load
@@ -285,7 +275,7 @@ __device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, co
   if (wave < NB) load_row_meta(a.w, mt, lane, rm);
   // ---- add the eight partial sums: wave j (< NB) finishes pixel block j
   __syncthreads();
-  SK_STAMP(4);
+  RMSMP_REG_STAMP(4);
   {
     int* dst = (int*)smem + wave * (NB * 16 * LANES);
 #pragma unroll
@@ -296,9 +286,9 @@ __device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, co
             (v4i){acc[j][4 * q], acc[j][4 * q + 1], acc[j][4 * q + 2], acc[j][4 * q + 3]};
   }
   __syncthreads();
-  SK_STAMP(5);
+  RMSMP_REG_STAMP(5);
   if (wave >= NB) {
-    SK_FLUSH();
+    RMSMP_REG_STAMPS_FLUSH();
     return;
   }
   v16i sum[1];
@@ -317,11 +307,11 @@ __device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, co
       sum[0][4 * q + 3] += got.w;
     }
   }
-  SK_STAMP(6);
+  RMSMP_REG_STAMP(6);
   const int64_t ncol[1] = {32 * wave + (lane & 31)};
   finish_tiles<1>(ea, KIND, sum, rm, lane_rows(tr.nvalid, lane), ncol);
-  SK_STAMP(7);
-  SK_FLUSH();
+  RMSMP_REG_STAMP(7);
+  RMSMP_REG_STAMPS_FLUSH();
 }
 
 template <int NB>
