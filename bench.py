@@ -5,7 +5,9 @@ One step = one pass of the whole hot path over one batch of configs[3]: the 20 c
 ResNet-18 at batch 64 and 224x224 (Section 4.2 / Table 6's workload, 232.1 GOP), each one
 rmsmp_conv2d call -- conv1 with Fixed-8 rows and 8-bit activations, the others with weight rows
 Fixed4:PoT4:Fixed8 = 60:35:5 and unsigned 4-bit activations resident in HBM, fused ReLU + 4-bit
-requantization -- launched back to back on one stream.  Prints one JSON line.
+requantization -- launched back to back on one stream; the first 3x3 layer of stages 2-4 and the
+stage's 1x1 shortcut projection read the same tensor and go out together as one
+rmsmp_conv2d_pair call (17 launches per step).  Prints one JSON line.
 
 Besides the contract fields the line carries: per-layer times, the time share of every kernel
 family, the same step with the batch cut in two halves on two streams, the other configurations (configs[1], configs[2], configs[4] with cold weights), the
@@ -35,6 +37,7 @@ def _conv_out(h, k, s, p):
 def make_stack(rm, si, torch, dev, batch, inv_scales=None):
     """Synthetic ResNet-18 conv stack: packed weights, resident inputs, output buffers, launchers."""
     layers = []
+    by_name = {}
     for idx, (name, C, M, k, s, pad, H) in enumerate(si.RESNET18_CONVS):
         rng = si.rng_for(3, idx)
         K = C * k * k
@@ -42,16 +45,21 @@ def make_stack(rm, si, torch, dev, batch, inv_scales=None):
         if idx == 0:  # first layer: Fixed-8 rows, signed 8-bit image (Section 4: first and last layers 8-bit)
             scheme = np.full(M, 2, np.uint8)
             x, s_x = si.symmetric_i8_from_float(rng.standard_normal((batch, H, H, C)))
-            bits, xdev = 8, x
+            bits = 8
         else:
             scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, 35, 60, 5))
-            x, s_x, bits = si.act_codes_u4(rng, (batch, H, H, C)), 0.05, 4
-            xdev = rm.pack_u4(x)
+            s_x, bits = 0.05, 4
+            x = None if name.endswith(".downsample") else si.act_codes_u4(rng, (batch, H, H, C))
         OH = _conv_out(H, k, s, pad)
         N = batch * OH * OH
         p = rm.rmsmp_pack_weights(W, scheme, taps=k * k)
         d = rm.ConvDesc(batch, C, H, H, k, k, s, pad)
-        X = torch.from_numpy(xdev).to(dev)
+        if x is None:
+            # the 1x1 projection of a stage's shortcut reads the stage's input: the tensor of its first 3x3 layer
+            head = by_name[name.replace(".downsample", ".conv1")]
+            x, X = head["x"], head["X"]
+        else:
+            X = torch.from_numpy(x if bits == 8 else rm.pack_u4(x)).to(dev)
         Y = torch.empty((N, M // 2), dtype=torch.uint8, device=dev)
         inv = np.float32(2.0 if inv_scales is None else inv_scales[idx])
         ep = rm.make_epilogue(s_x, 0, bits, None, True, rm.OUT_U4, inv)
@@ -60,7 +68,37 @@ def make_stack(rm, si, torch, dev, batch, inv_scales=None):
         layers.append(dict(idx=idx, name=name, C=C, M=M, k=k, s=s, pad=pad, H=H, OH=OH, N=N, K=K, W=W, scheme=scheme,
                            x=x, s_x=s_x, bits=bits, p=p, d=d, X=X, Y=Y, ep=ep, inv=inv, ws=ws, ops=2.0 * M * K * N,
                            launch=rm.conv2d_launcher(p, X, d, ep, Y, ws)))
+        by_name[name] = layers[-1]
     return layers
+
+
+def launch_units(rm, layers, stream=None, batch=None, part=0):
+    """The launches of one step, in layer order: one rmsmp_conv2d per layer, except that a stage's
+    first 3x3 layer and its shortcut projection (same input) go out together as one
+    rmsmp_conv2d_pair.  batch / part: only images part*batch .. (part+1)*batch-1 (same buffers)."""
+    units, by_name, taken = [], {L["name"]: L for L in layers}, set()
+
+    def view(L):
+        if batch is None:
+            return L["d"], L["X"], L["Y"]
+        n = L["N"] // (L["d"].B // batch)
+        return (rm.ConvDesc(batch, L["C"], L["H"], L["H"], L["k"], L["k"], L["s"], L["pad"]),
+                L["X"][part * batch:(part + 1) * batch], L["Y"][part * n:(part + 1) * n])
+
+    for L in layers:
+        if L["name"] in taken:
+            continue
+        side = by_name.get(L["name"].replace(".conv1", ".downsample")) if L["name"].endswith(".0.conv1") else None
+        if side is not None and L["ws"] is None and side["ws"] is None:
+            (da, Xa, Ya), (db, _, Yb) = view(L), view(side)
+            units.append(dict(layers=[L, side], launch=rm.conv2d_pair_launcher(L["p"], da, L["ep"], Ya, side["p"], db, side["ep"], Yb, Xa, stream=stream)))
+            taken.add(side["name"])
+        else:
+            if batch is not None and L["ws"] is not None:
+                raise SystemExit("bench.py: a layer with an im2col workspace cannot be shared by two streams")
+            d, X, Y = view(L)
+            units.append(dict(layers=[L], launch=rm.conv2d_launcher(L["p"], X, d, L["ep"], Y, L["ws"], stream=stream)))
+    return units
 
 
 def kernel_of(rm, layer):
@@ -136,17 +174,22 @@ def check_against_oracle(rm, oracle, torch, layers):
             sys.exit(1)
 
 
-def time_block(torch, fns, iters, warm):
+def time_block(torch, fns, iters, warm, reps=5):
+    """Microseconds per launch: the median over reps blocks of iters back-to-back launches, each
+    block between two events on the launch stream (a single block can catch a clock or power step)."""
     for i in range(warm):
         fns[i % len(fns)]()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(iters):
-        fns[i % len(fns)]()
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) * 1e3 / iters  # microseconds per launch
+    times = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(iters):
+            fns[i % len(fns)]()
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1) * 1e3 / iters)
+    return float(np.median(times))
 
 
 def other_configs(rm, si, torch, dev):
@@ -219,14 +262,8 @@ def two_stream_schedule(rm, torch, layers, steps, warm):
     expect = [L["Y"].clone() for L in layers]
     for L in layers:
         L["Y"].zero_()
-    launchers = []
-    for L in layers:
-        if L["ws"] is not None:
-            raise SystemExit("bench.py: a layer with an im2col workspace cannot be shared by two streams")
-        d = rm.ConvDesc(half, L["C"], L["H"], L["H"], L["k"], L["k"], L["s"], L["pad"])
-        n = L["N"] // 2
-        launchers.append([rm.conv2d_launcher(L["p"], L["X"][i * half:(i + 1) * half], d, L["ep"], L["Y"][i * n:(i + 1) * n],
-                                             L["ws"], stream=streams[i]) for i in range(2)])
+    halves = [launch_units(rm, layers, stream=streams[i], batch=half, part=i) for i in range(2)]
+    launchers = list(zip(*[[u["launch"] for u in h] for h in halves]))
     torch.cuda.synchronize()
 
     def step():
@@ -246,7 +283,7 @@ def two_stream_schedule(rm, torch, layers, steps, warm):
     if not same:
         raise SystemExit("bench.py: the two-stream schedule's outputs differ from the one-stream step's")
     ops = sum(L["ops"] for L in layers)
-    return {"ms_per_step": round(ms, 6), "tops": round(ops / (ms * 1e-3) / 1e12, 2), "launches_per_step": 2 * len(layers),
+    return {"ms_per_step": round(ms, 6), "tops": round(ops / (ms * 1e-3) / 1e12, 2), "launches_per_step": 2 * len(launchers),
             "outputs_identical_to_one_stream_step": same,
             "note": "batch 64 as two halves of 32 on two streams, layer order kept per image; not the headline "
                     "(the headline is the one-stream step that the kernel trace and the per-layer times describe)"}
@@ -307,7 +344,8 @@ def main():
             L["inv"] = inv
             L["ep"] = rm.make_epilogue(L["s_x"], 0, L["bits"], None, True, rm.OUT_U4, inv)
             L["launch"] = rm.conv2d_launcher(L["p"], L["X"], L["d"], L["ep"], L["Y"], L["ws"])
-    launchers = [L["launch"] for L in layers]
+    units = launch_units(rm, layers)
+    launchers = [u["launch"] for u in units]
     total_ops = sum(L["ops"] for L in layers)
 
     def step():
@@ -332,26 +370,48 @@ def main():
     if base is not None:
         check_against_oracle(rm, oracle, torch, layers)
 
-    # per-layer times: every layer alone, back to back, between two events
-    per_layer, families = {}, {}
+    # per-layer times: every layer alone, back to back, between two events (also the two layers of a pair)
+    per_layer = {}
     for L in layers:
         L["kernel"] = kernel_of(rm, L)
     torch.cuda.synchronize()
     for L in layers:
-        us = time_block(torch, [L["launch"]], args.layer_iters, 10)
-        L["us"] = us
-        per_layer[L["name"]] = dict(us=round(us, 3), tops=round(L["ops"] / us / 1e6, 1), kernel=L["kernel"])
-        fam = families.setdefault(L["kernel"], dict(us=0.0, ops=0.0, launches=0))
-        fam["us"] += us
-        fam["ops"] += L["ops"]
-        fam["launches"] += 1
-    sum_us = sum(L["us"] for L in layers)
+        L["us"] = time_block(torch, [L["launch"]], args.layer_iters, 10)
+        per_layer[L["name"]] = dict(us=round(L["us"], 3), tops=round(L["ops"] / L["us"] / 1e6, 1), kernel=L["kernel"])
+    # the launches of the step, each alone; a fused pair is a kernel family of its own
+    families, fused = {}, {}
+    for u in units:
+        if len(u["layers"]) == 2:
+            u["launch"]()
+            kernel, _ = rm.rmsmp_debug_last_dispatch()
+            if kernel == "lds_resident_pair":
+                u["kernel"] = "rmsmp::conv_wide_pair_kernel<%d>" % (u["layers"][0]["C"] // 32)
+                u["us"] = time_block(torch, [u["launch"]], args.layer_iters, 10)
+                a, b = u["layers"]
+                fused[a["name"] + " + " + b["name"]] = dict(us=round(u["us"], 3), one_after_the_other_us=round(a["us"] + b["us"], 3),
+                                                            tops=round((a["ops"] + b["ops"]) / u["us"] / 1e6, 1), kernel=u["kernel"])
+                for L in u["layers"]:
+                    per_layer[L["name"]]["in_the_step"] = "one launch with its partner: " + u["kernel"]
+                parts = [(u["kernel"], u["us"], a["ops"] + b["ops"])]
+            else:  # the library launched the two layers one after the other
+                parts = [(L["kernel"], L["us"], L["ops"]) for L in u["layers"]]
+        else:
+            L = u["layers"][0]
+            u["kernel"] = L["kernel"]
+            parts = [(L["kernel"], L["us"], L["ops"])]
+        for kname, us, ops in parts:
+            fam = families.setdefault(kname, dict(us=0.0, ops=0.0, launches=0))
+            fam["us"] += us
+            fam["ops"] += ops
+            fam["launches"] += 1
+    sum_us = sum(v["us"] for v in families.values())
     share = {k: round(v["us"] / sum_us, 4) for k, v in sorted(families.items(), key=lambda kv: -kv[1]["us"])}
     dom_name = max(families, key=lambda k: families[k]["us"])
-    dom_layers = [L for L in layers if L["kernel"] == dom_name]
-    # the dominant kernel's average launch duration: its layers round-robin, back to back, between two events
-    dom_us = time_block(torch, [L["launch"] for L in dom_layers], max(1, args.layer_iters // 2) * len(dom_layers), 4 * len(dom_layers))
-    dom_ops = sum(L["ops"] for L in dom_layers) / len(dom_layers)
+    dom_units = [u for u in units if u.get("kernel") == dom_name]
+    # the dominant kernel's average launch duration: its launches round-robin, back to back, between two events
+    dom_us = time_block(torch, [u["launch"] for u in dom_units], max(1, args.layer_iters // 2) * len(dom_units), 4 * len(dom_units))
+    dom_ops = sum(L["ops"] for u in dom_units for L in u["layers"]) / len(dom_units)
+    dom_layers = [L for u in dom_units for L in u["layers"]]
     achieved = dom_ops / dom_us / 1e6
 
     out = {
@@ -362,14 +422,17 @@ def main():
         "pct_of_int8_mfma_peak": round(100.0 * tops / INT8_MFMA_PEAK_TOPS, 2),
         "config": {"workload": "configs[3]: full ResNet-18 conv stack, batch 64, 224x224: 20 conv layers (232.1 GOP per step), "
                                "conv1 Fixed-8 rows x int8 activations, the others rows Fixed4:PoT4:Fixed8 = 60:35:5 x uint4 "
-                               "activations, each one rmsmp_conv2d launch with fused ReLU + uint4 requant, back to back on one stream",
-                   "gop_per_step": round(total_ops / 1e9, 2), "launches_per_step": len(layers),
+                               "activations, fused ReLU + uint4 requant; one rmsmp_conv2d launch per layer, except that the first 3x3 layer of "
+                               "stages 2-4 and the stage's 1x1 shortcut projection (same input tensor) go out as one "
+                               "rmsmp_conv2d_pair launch; back to back on one stream",
+                   "gop_per_step": round(total_ops / 1e9, 2), "launches_per_step": len(units),
                    "gpu_events_ms_per_step": round(gpu_ms / args.steps, 6)},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4), "traffic": traffic_from_profile(dom_name),
                      "kernel": dom_name, "avg_launch_us": round(dom_us, 3), "gop_per_launch": round(dom_ops / 1e9, 3),
                      "layers": [L["name"] for L in dom_layers], "time_share_by_kernel": share},
         "per_layer": per_layer,
+        "fused_pairs": fused,
         "cpu_baseline": base,
     }
     if not args.no_extras:

@@ -190,6 +190,28 @@ rmsmp_status rmsmp_conv2d_workspace_size(const rmsmp_packed* Wp, const rmsmp_con
                                          int32_t act_bits, size_t* bytes);
 
 /*
+ * Two convolutions that read the same input tensor, enqueued together: layer A then layer B,
+ * each exactly as rmsmp_conv2d computes it (Alg. 1 forward line, once per layer).  Meant for
+ * the head of a residual stage of the ResNet-18 workload (Section 4.2): the stride-2 3x3
+ * convolution and the stride-2 1x1 projection of the shortcut both read the stage's input.
+ * When A is a 3x3 layer and B a 1x1 layer with the same 64, 128 or 256 input channels, 4-bit
+ * activations, output kinds 0..2 and shapes the LDS-resident kernel takes, the two run as ONE
+ * launch whose work-groups share the compute units (the short 1x1 layer runs in the shadow of
+ * the 3x3 layer instead of paying a launch of its own); otherwise the library launches A and
+ * then B on the stream.  Results are identical either way.
+ *
+ *   WpA, dA, epA, YA / WpB, dB, epB, YB   as for rmsmp_conv2d; dA and dB must agree in B, C, H, W,
+ *        epA and epB in act_scale, act_zero_point and act_bits; YA != YB.
+ *   X    DEVICE, the common input (NHWC codes), 16-byte aligned.
+ * Asynchronous on `stream`; allocates nothing; no workspace: a layer that would need one
+ * (rmsmp_conv2d_workspace_size > 0) is refused with EWORKSPACE.
+ * Errors: as rmsmp_conv2d, plus ESHAPE / EINVAL when the two layers disagree on the input.
+ */
+rmsmp_status rmsmp_conv2d_pair(const rmsmp_packed* WpA, const rmsmp_conv_desc* dA, const rmsmp_epilogue* epA, void* YA,
+                               const rmsmp_packed* WpB, const rmsmp_conv_desc* dB, const rmsmp_epilogue* epB, void* YB,
+                               const void* X, void* stream);
+
+/*
  * rmsmp_conv2d for callers that cannot allocate device memory: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
  * rmsmp_conv2d, minus the workspace: layers that need one (see rmsmp_conv2d) materialise their
@@ -252,7 +274,8 @@ rmsmp_status rmsmp_ste_backward(const float* W, const float* alpha, const float*
  * rmsmp_debug_last_dispatch -- what the calling thread's last rmsmp_gemm / rmsmp_conv2d ran:
  *   out (HOST, 5 entries) = {kernel, pixel_blocks, k_split, side_by_side, tile_pairs} with kernel
  *   0 none, 1 general, 2 skinny (N <= 64), 3 small-channel rows, 4 first layer (3 channels,
- *   stride 2), 5 LDS-resident; the other four are 0 unless kernel == 5.
+ *   stride 2), 5 LDS-resident, 6 LDS-resident with two layers in one launch (rmsmp_conv2d_pair);
+ *   the other four are 0 unless kernel == 5.
  * Errors: EINVAL (negative value, NULL).
  */
 rmsmp_status rmsmp_debug_set_wave_split(int32_t pixel_blocks, int32_t k_split, int32_t side_by_side,

@@ -165,7 +165,8 @@ def main():
             us, ops = conv_case(3, i, 64)
             tot_us += us
             tot_ops += ops
-        print("cfg3 ResNet-18 conv stack, batch 64: %.3f ms, %.1f TOPS (%.1f GOP)"
+        # (the sum of the 20 layers timed one by one; bench.py times the step itself, back to back)
+        print("cfg3 ResNet-18 conv stack, batch 64, sum of the layers timed one by one: %.3f ms, %.1f TOPS (%.1f GOP)"
               % (tot_us / 1e3, tot_ops / tot_us / 1e6, tot_ops / 1e9), flush=True)
     if "skinny" in which:
         for N in (1, 8, 64):

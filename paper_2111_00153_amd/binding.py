@@ -54,7 +54,8 @@ EXPORTS = ["rmsmp_last_error", "rmsmp_version", "rmsmp_ratio_counts", "rmsmp_ass
            "rmsmp_pack_weights", "rmsmp_free_packed", "rmsmp_packed_info", "rmsmp_unpack_codes",
            "rmsmp_pack_roundtrip_host", "rmsmp_gemm", "rmsmp_conv2d", "rmsmp_conv2d_workspace_size",
            "rmsmp_fake_quant_rows", "rmsmp_ste_backward", "rmsmp_debug_set_wave_split",
-           "rmsmp_debug_last_dispatch", "rmsmp_debug_measure_peaks", "rmsmp_init", "rmsmp_conv2d_static_workspace", "rmsmp_debug_gelu_breakpoints"]
+           "rmsmp_debug_last_dispatch", "rmsmp_debug_measure_peaks", "rmsmp_init", "rmsmp_conv2d_static_workspace", "rmsmp_debug_gelu_breakpoints",
+           "rmsmp_conv2d_pair"]
 
 
 def _check(rc):
@@ -204,6 +205,26 @@ def rmsmp_conv2d_static_workspace(p, X, d, ep, Y, stream=None):
                                               _stream(stream)))
 
 
+def rmsmp_conv2d_pair(pa, da, epa, Ya, pb, db, epb, Yb, X, stream=None):
+    """Two convolutions on the same input X, enqueued together (one launch where the library can)."""
+    _check(_lib.rmsmp_conv2d_pair(pa.handle, ctypes.byref(da), ctypes.byref(epa), _dev(Ya),
+                                  pb.handle, ctypes.byref(db), ctypes.byref(epb), _dev(Yb), _dev(X), _stream(stream)))
+
+
+def conv2d_pair_launcher(pa, da, epa, Ya, pb, db, epb, Yb, X, stream=None):
+    """rmsmp_conv2d_pair with the arguments marshalled once (see conv2d_launcher)."""
+    args = (pa.handle, ctypes.byref(da), ctypes.byref(epa), _dev(Ya), pb.handle, ctypes.byref(db), ctypes.byref(epb),
+            _dev(Yb), _dev(X), _stream(stream))
+    fn = _lib.rmsmp_conv2d_pair
+
+    def launch():
+        rc = fn(*args)
+        if rc:
+            _check(rc)
+    launch.keepalive = (pa, da, epa, Ya, pb, db, epb, Yb, X)
+    return launch
+
+
 def conv2d_launcher(p, X, d, ep, Y, workspace=None, stream=None):
     """rmsmp_conv2d with the arguments marshalled once: returns a zero-argument callable that
     enqueues the same call again (for launch-bound loops and graph capture)."""
@@ -250,7 +271,7 @@ def rmsmp_debug_set_wave_split(pixel_blocks=0, k_split=0, side_by_side=0, tile_p
     _check(_lib.rmsmp_debug_set_wave_split(int(pixel_blocks), int(k_split), int(side_by_side), int(tile_pairs)))
 
 
-KERNEL_NAMES = ("none", "general", "skinny", "rows", "first_layer", "lds_resident")
+KERNEL_NAMES = ("none", "general", "skinny", "rows", "first_layer", "lds_resident", "lds_resident_pair")
 
 
 def rmsmp_debug_last_dispatch():

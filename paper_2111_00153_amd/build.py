@@ -15,6 +15,9 @@ WIDE_FAMILIES = [(9, 2), (9, 4), (9, 8), (9, 16), (1, 2), (1, 4), (1, 8), (1, 16
 # channel counts (in K steps) whose 1x1 family also exists as the variant that stages a deeper layer in parts
 WIDE_DEEP_FAMILIES = [16, 24]
 WIDE_SOURCE = "csrc/patch_wide_inst.hip"
+# channel counts (in K steps) the two-layer launch (a 3x3 and a 1x1 layer on one input) is built for
+WIDE_PAIR_FAMILIES = [2, 4, 8]
+WIDE_PAIR_SOURCE = "csrc/patch_wide_pair.hip"
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed-FP32 VALU forms are kept off (per-lane fp32 epilogue must be bit-reproducible)
@@ -31,6 +34,8 @@ def _units():
     for cpt in WIDE_DEEP_FAMILIES:
         units.append((WIDE_SOURCE, ["-DRMSMP_WIDE_TAPS=1", "-DRMSMP_WIDE_CPT=%d" % cpt, "-DRMSMP_WIDE_DEEP=1"],
                       os.path.join(OBJ_DIR, "patch_wide_inst_deep_%d.o" % cpt)))
+    for cpt in WIDE_PAIR_FAMILIES:
+        units.append((WIDE_PAIR_SOURCE, ["-DRMSMP_WIDE_CPT=%d" % cpt], os.path.join(OBJ_DIR, "patch_wide_pair_%d.o" % cpt)))
     return units
 
 
@@ -44,7 +49,7 @@ def is_stale():
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(os.path.join(HERE, f)) > t for f in SOURCES + [WIDE_SOURCE] + HEADERS)
+    return any(os.path.getmtime(os.path.join(HERE, f)) > t for f in SOURCES + [WIDE_SOURCE, WIDE_PAIR_SOURCE] + HEADERS)
 
 
 def build_library(force=True, only_changed=False, extra=()):

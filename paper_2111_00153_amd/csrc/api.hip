@@ -396,6 +396,58 @@ rmsmp_status rmsmp_conv2d(const rmsmp_packed* Wp, const void* X, const rmsmp_con
   return RMSMP_OK;
 }
 
+// Both layers are checked as rmsmp_conv2d checks them; then one launch if the pair kernel takes
+// them, else the two layers one after the other.
+rmsmp_status rmsmp_conv2d_pair(const rmsmp_packed* WpA, const rmsmp_conv_desc* dA, const rmsmp_epilogue* epA, void* YA,
+                               const rmsmp_packed* WpB, const rmsmp_conv_desc* dB, const rmsmp_epilogue* epB, void* YB,
+                               const void* X, void* stream) {
+  if (!WpA || !WpB) return fail(RMSMP_EINVAL, "conv2d_pair: NULL packed weights");
+  if (!dA || !dB) return fail(RMSMP_EINVAL, "conv2d_pair: NULL convolution descriptor");
+  if (dA->B != dB->B || dA->C != dB->C || dA->H != dB->H || dA->W != dB->W)
+    return fail(RMSMP_ESHAPE, "conv2d_pair: the two layers must read the same input tensor (B, C, H, W)");
+  if (!epA || !epB) return fail(RMSMP_EINVAL, "epilogue is NULL");
+  if (epA->act_bits != epB->act_bits || epA->act_zero_point != epB->act_zero_point || epA->act_scale != epB->act_scale)
+    return fail(RMSMP_EINVAL, "conv2d_pair: the two layers must agree on the input's scale, zero point and width");
+  if (YA == YB && YA) return fail(RMSMP_EINVAL, "conv2d_pair: the two outputs must be different buffers");
+  const rmsmp_packed* Wp[2] = {WpA, WpB};
+  const rmsmp_conv_desc* d[2] = {dA, dB};
+  const rmsmp_epilogue* ep[2] = {epA, epB};
+  void* Y[2] = {YA, YB};
+  rmsmp::GemmArgs a[2];
+  for (int i = 0; i < 2; ++i) {
+    rmsmp_status st = check_epilogue(ep[i], Wp[i]->host.M);
+    if (st != RMSMP_OK) return st;
+    int OH, OW;
+    st = conv_geometry(Wp[i], d[i], ep[i]->act_bits, &OH, &OW);
+    if (st != RMSMP_OK) return st;
+    if (!X || !Y[i]) return fail(RMSMP_EINVAL, "conv2d_pair: NULL X or Y");
+    if (((uintptr_t)X & 15) != 0) return fail(RMSMP_EINVAL, "conv2d_pair: X must be 16-byte aligned");
+    if (!conv_is_implicit(Wp[i], d[i], ep[i]->act_bits))
+      return fail(RMSMP_EWORKSPACE, "conv2d_pair: a layer that needs an im2col workspace cannot be part of a pair; use rmsmp_conv2d");
+    a[i].w = Wp[i]->dev;
+    a[i].M = Wp[i]->host.M;
+    a[i].K = Wp[i]->host.K;
+    a[i].N = (int64_t)d[i]->B * OH * OW;
+    a[i].X = X;
+    a[i].Y = Y[i];
+    a[i].ep = *ep[i];
+    a[i].d = *d[i];
+    a[i].OH = OH;
+    a[i].OW = OW;
+    a[i].conv = 1;
+    fill_gelu_table(*ep[i], &a[i]);
+  }
+  bool fused = false;
+  hipError_t e = (hipError_t)rmsmp::try_launch_wide_pair(a[0], a[1], stream, &fused);
+  if (e != hipSuccess) return hip_fail(e, "conv2d_pair: kernel launch");
+  if (fused) return RMSMP_OK;
+  for (int i = 0; i < 2; ++i) {
+    e = (hipError_t)rmsmp::launch_gemm(a[i], stream);
+    if (e != hipSuccess) return hip_fail(e, "conv2d_pair: kernel launch");
+  }
+  return RMSMP_OK;
+}
+
 rmsmp_status rmsmp_init(void) {
   void* ws = nullptr;
   return static_workspace(&ws);

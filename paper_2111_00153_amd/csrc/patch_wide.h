@@ -583,6 +583,18 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
       }
       continue;
     }
+    if constexpr (WIDE_GELU) {
+      // the GELU epilogue holds twice the values per output: one block at a time, in a path of its own
+      if (ea.out_kind == 3) {
+#pragma unroll
+        for (int o = 0; o < BPT; ++o) {
+          const int64_t ncol[1] = {col0 + 32 * o};
+          const v16i blocks[1] = {mine[ti * BPT + o]};
+          finish_tiles<1, RowMetaLds, true>(ea, kind, blocks, rm, n_rows, ncol);
+        }
+        continue;
+      }
+    }
 #pragma unroll
     for (int c0 = 0; c0 < BPT; c0 += CH) {
       int64_t ncol[CH];
@@ -592,20 +604,22 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
         ncol[o] = col0 + 32 * (c0 + o);
         blocks[o] = mine[ti * BPT + c0 + o];
       }
-      finish_tiles<CH, RowMetaLds, WIDE_GELU>(ea, kind, blocks, rm, n_rows, ncol);
+      finish_tiles<CH, RowMetaLds, false>(ea, kind, blocks, rm, n_rows, ncol);
     }
   }
   RMSMP_PHASE(6);
 }
 
+// block_id: the work-group's number within its layer (the launch's own work-group id, except in a
+// launch that carries two layers)
 template <int TAPS, int CPT, int XB, int KS, int NWT, int MS, bool DEEP>
-__device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGeom& g) {
+__device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGeom& g, const unsigned block_id) {
   RMSMP_PHASE(0);
   // Work-group id -> (pixel tile bx, row block by).  Consecutive ids go to different XCDs, each
   // with its own L2, so the gy work-groups that read the same input patch get ids that are equal
   // modulo 8 and follow each other on that XCD: the patch comes out of memory once, not gy
   // times.  The grid is padded to a multiple of 8 pixel tiles; the extra work-groups leave.
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int xcd = block_id & 7, slot = block_id >> 3;
   const int by = slot % g.gy;
   const int bx = (slot / g.gy) * 8 + xcd;
   if (bx >= g.gx) return;
@@ -657,7 +671,33 @@ __device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGe
 
 template <int TAPS, int CPT, int XB, int KS, int NWT, int MS, bool DEEP>
 __global__ __launch_bounds__(LANES * KS * NWT * MS, KS * NWT * MS == 8 ? 1 : 2) void conv_wide_kernel(GemmArgs a, WideGeom g) {
-  wide_kernel_impl<TAPS, CPT, XB, KS, NWT, MS, DEEP>(a, g);
+  wide_kernel_impl<TAPS, CPT, XB, KS, NWT, MS, DEEP>(a, g, blockIdx.x);
+}
+
+// Two layers that read the same input tensor as one launch: a 3x3 layer and a 1x1 layer with the
+// same channel count (the two convolutions at the head of a residual stage, Section 4.2's
+// ResNet-18: the stride-2 3x3 convolution and the stride-2 1x1 projection of the shortcut).  The
+// first blocks_a work-groups run the 3x3 layer's code, the others the 1x1 layer's; the two kinds
+// share compute units, so the short 1x1 work-groups run in the shadow of the long ones instead
+// of paying a launch of their own.  Neither layer may use the GELU epilogue (its table is read
+// from the start of the kernel arguments).
+struct WidePairSplit {
+  int xa, ka, na, ma;  // 3x3 layer: pixel blocks per wave, K split, side by side, tile pairs
+  int xb, kb, nb, mb;  // 1x1 layer
+};
+// the splits the pair kernel is built with, per channel count / 32: those the single-layer model
+// picks for the ResNet-18 stage heads at batch 64
+constexpr WidePairSplit wide_pair_split(int cpt) {
+  return cpt == 2 ? WidePairSplit{4, 2, 1, 2, 2, 1, 4, 1} : cpt == 4 ? WidePairSplit{2, 1, 1, 4, 2, 1, 1, 4} : WidePairSplit{2, 2, 1, 2, 2, 2, 1, 2};
+}
+
+template <int CPT>
+__global__ __launch_bounds__(LANES * 4, 2) void conv_wide_pair_kernel(GemmArgs a, WideGeom ga, GemmArgs b, WideGeom gb, unsigned blocks_a) {
+  constexpr WidePairSplit sp = wide_pair_split(CPT);
+  if (blockIdx.x < blocks_a)
+    wide_kernel_impl<9, CPT, sp.xa, sp.ka, sp.na, sp.ma, false>(a, ga, blockIdx.x);
+  else
+    wide_kernel_impl<1, CPT, sp.xb, sp.kb, sp.nb, sp.mb, false>(b, gb, blockIdx.x - blocks_a);
 }
 
 struct WidePlan {
@@ -679,6 +719,15 @@ inline int launch_wide_t(const WidePlan& p, hipStream_t s) {
     hipLaunchKernelGGL((conv_wide_kernel<TAPS, CPT, XB, KS, NWT, MS, DEEP>), dim3(p.blocks), dim3(LANES * KS * NWT * MS), p.lds, s, p.a, p.g);
     return (int)hipGetLastError();
   }
+}
+
+template <int CPT>
+inline int launch_wide_pair_t(const WidePlan& pa, const WidePlan& pb, hipStream_t s) {
+  static std::atomic<uint64_t> allowed{0};
+  if (const int rc = allow_large_lds((const void*)conv_wide_pair_kernel<CPT>, allowed)) return rc;
+  const size_t lds = pa.lds > pb.lds ? pa.lds : pb.lds;
+  hipLaunchKernelGGL((conv_wide_pair_kernel<CPT>), dim3(pa.blocks + pb.blocks), dim3(LANES * 4), lds, s, pa.a, pa.g, pb.a, pb.g, pa.blocks);
+  return (int)hipGetLastError();
 }
 
 template <int TAPS, int CPT, bool DEEP>

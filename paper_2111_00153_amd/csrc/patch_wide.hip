@@ -21,6 +21,13 @@ RMSMP_WIDE_FAMILIES(RMSMP_WIDE_DECL)
 RMSMP_WIDE_DEEP_FAMILIES(RMSMP_WIDE_DECL)
 #undef RMSMP_WIDE_DECL
 
+#ifndef RMSMP_WIDE_PAIR_FAMILIES  // channel counts / 32 the two-layer launch exists for
+#define RMSMP_WIDE_PAIR_FAMILIES(X) X(2) X(4) X(8)
+#endif
+#define RMSMP_WIDE_DECL(CP) int launch_wide_pair_##CP(const WidePlan& pa, const WidePlan& pb, hipStream_t s);
+RMSMP_WIDE_PAIR_FAMILIES(RMSMP_WIDE_DECL)
+#undef RMSMP_WIDE_DECL
+
 static uint32_t wide_div_magic(int64_t d) {
   return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + (uint64_t)d - 1) / (uint64_t)d);
 }
@@ -89,9 +96,12 @@ static bool wide_cpt_supported(int taps, int cpt) {
   return cpt == 2 || cpt == 4 || cpt == 8 || cpt == 16 || cpt == 24;
 }
 
-static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
+// Whether the layer is one the kernel takes at all.  *a_out: the layer as a convolution (a plain
+// GEMM becomes a 1x1 convolution over N single-pixel images); *cc_out: channels staged at a time.
+static bool wide_layer_fits(const GemmArgs& a0, GemmArgs* a_out, int* cc_out) {
   if (a0.ep.act_bits != 4) return false;
-  GemmArgs a = a0;
+  GemmArgs& a = *a_out;
+  a = a0;
   if (!a.conv) {
     if (a.K % (2 * KSTEP) != 0 || a.K > 64 * 768 || a.N >= ((int64_t)1 << 30)) return false;
     a.conv = 1;
@@ -125,6 +135,16 @@ static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
   const int64_t row_extra = S * ((int64_t)a.d.W - a.OW);
   const int64_t img_extra = (int64_t)a.d.W * ((int64_t)a.d.H - S * a.OH);
   if (row_extra < 0 || row_extra + img_extra < 0) return false;
+  *cc_out = cc;
+  return true;
+}
+
+static bool wide_kernel_applies(const GemmArgs& a0, WidePlan* plan) {
+  GemmArgs a;
+  int cc = 0;
+  if (!wide_layer_fits(a0, &a, &cc)) return false;
+  const int taps = a.d.KH * a.d.KW;
+  const int cpt = cc / KSTEP, nchunk = a.d.C / cc;
   const int n_pairs = (a.w.n_tiles + 1) / 2;
   // How the four waves are shared out: the candidate with the lowest estimated time wins.  The
   // estimate is a per-work-group critical path (cycles; the constants started from per-phase clock
@@ -205,6 +225,37 @@ int try_launch_wide(const GemmArgs& a, void* stream, bool* applied) {
   rec.kernel = 5;
   rec.xb = plan.xb, rec.ks = plan.ks, rec.nwt = plan.nwt, rec.ms = plan.ms;
   return launch_wide(plan, (hipStream_t)stream);
+}
+
+// Two layers on the same input as one launch (see conv_wide_pair_kernel): a 3x3 layer and a 1x1
+// layer with the same 64, 128 or 256 input channels, both with 4-bit activations, neither with
+// the GELU epilogue, each fitting the split the pair kernel is built with.  *applied says whether
+// the launch happened; if not, the caller launches the layers one after the other.
+int try_launch_wide_pair(const GemmArgs& a0, const GemmArgs& b0, void* stream, bool* applied) {
+  *applied = false;
+  GemmArgs a, b;
+  int cca = 0, ccb = 0;
+  if (a0.X != b0.X || !a0.conv || !b0.conv) return 0;
+  if (a0.ep.out_kind == 3 || b0.ep.out_kind == 3) return 0;
+  if (!wide_layer_fits(a0, &a, &cca) || !wide_layer_fits(b0, &b, &ccb)) return 0;
+  if (a.d.KH * a.d.KW != 9 || b.d.KH * b.d.KW != 1) return 0;
+  if (a.d.C != b.d.C || cca != a.d.C || ccb != b.d.C) return 0;
+  const int cpt = a.d.C / KSTEP;
+  if (cpt != 2 && cpt != 4 && cpt != 8) return 0;
+  const WidePairSplit sp = wide_pair_split(cpt);
+  if ((a.w.n_tiles + 1) / 2 < sp.ma || (b.w.n_tiles + 1) / 2 < sp.mb) return 0;
+  WidePlan pa, pb;
+  if (!wide_plan_mode(a, cca, sp.xa, sp.ka, sp.na, sp.ma, &pa) || !wide_plan_mode(b, ccb, sp.xb, sp.kb, sp.nb, sp.mb, &pb)) return 0;
+  if ((uint64_t)pa.blocks + pb.blocks > 0x7fffffffu) return 0;
+  *applied = true;
+  DispatchRecord& rec = last_dispatch();
+  rec.kernel = 6;
+  rec.xb = 0, rec.ks = 0, rec.nwt = 0, rec.ms = 0;
+#define RMSMP_WIDE_CASE(CP) \
+  if (cpt == CP) return launch_wide_pair_##CP(pa, pb, (hipStream_t)stream);
+  RMSMP_WIDE_PAIR_FAMILIES(RMSMP_WIDE_CASE)
+#undef RMSMP_WIDE_CASE
+  return (int)hipErrorInvalidValue;
 }
 
 }  // namespace rmsmp

@@ -169,7 +169,7 @@ int launch_ste_backward(const SteArgs& a, void* stream);
 // automatic); like last_dispatch() it belongs to the calling thread.
 // last_dispatch(): which kernel the calling thread's last launch_gemm went to.
 struct DispatchRecord {
-  int kernel = 0;  // 0 none, 1 general, 2 skinny, 3 small-channel rows, 4 first layer, 5 LDS-resident
+  int kernel = 0;  // 0 none, 1 general, 2 skinny, 3 small-channel rows, 4 first layer, 5 LDS-resident, 6 LDS-resident, two layers in one launch
   int xb = 0, ks = 0, nwt = 0, ms = 0;
 };
 int* forced_split();
@@ -180,6 +180,8 @@ int launch_gemm(const GemmArgs& a, void* stream);
 // LDS-resident implicit-im2col kernel (patch_wide.hip): launches when the layer fits it and says
 // so in *applied.
 int try_launch_wide(const GemmArgs& a, void* stream, bool* applied);
+// The same kernel for two layers that read one input (a 3x3 and a 1x1 layer), as one launch.
+int try_launch_wide_pair(const GemmArgs& a, const GemmArgs& b, void* stream, bool* applied);
 // First-layer kernel (conv_first.hip): 3 input channels, 8-bit activations, stride 2; same convention.
 int try_launch_conv_first(const GemmArgs& a, void* stream, bool* applied);
 int launch_im2col(const Im2colArgs& a, void* stream);
