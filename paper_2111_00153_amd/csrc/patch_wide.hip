@@ -107,6 +107,15 @@ static bool wide_layer_fits(const GemmArgs& a0, GemmArgs* a_out, int* cc_out) {
     a.conv = 1;
     a.d = rmsmp_conv_desc{(int32_t)a.N, (int32_t)a.K, 1, 1, 1, 1, 1, 0};
     a.OH = a.OW = 1;
+    // A K that no 1x1 family takes, neither whole nor in parts, but that is nine times a channel
+    // count of the 3x3 families (576, 1152: the lowered matrices of 3x3 layers): the same numbers
+    // are a 3x3 convolution without padding over N images of 3x3 pixels -- column n of X is image
+    // n, K index (tap, channel) -- which is the order a plain GEMM's weights are stored in.
+    const int64_t c9 = a.K / 9;
+    const bool as_1x1 = wide_cpt_supported(1, (int)(a.K / KSTEP)) || a.K % 768 == 0 || a.K % 512 == 0;
+    if (!as_1x1 && a.K % 9 == 0 && c9 % KSTEP == 0 && wide_cpt_supported(9, (int)(c9 / KSTEP)) && a.N * 9 < ((int64_t)1 << 31)) {
+      a.d = rmsmp_conv_desc{(int32_t)a.N, (int32_t)c9, 3, 3, 3, 3, 1, 0};
+    }
   }
   const int taps = a.d.KH * a.d.KW;
   if (!(taps == 1 || (a.d.KH == 3 && a.d.KW == 3))) return false;

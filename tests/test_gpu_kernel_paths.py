@@ -111,9 +111,11 @@ def test_lds_resident_kernel_every_wave_split(rm, oracle, split, geom, M):
 
 
 @pytest.mark.parametrize("split", SPLITS)
-@pytest.mark.parametrize("M,K,N", [(333, 768, 300), (96, 256, 1000), (130, 128, 129)])
+@pytest.mark.parametrize("M,K,N", [(333, 768, 300), (96, 256, 1000), (130, 128, 129), (100, 576, 300), (70, 1152, 129)])
 def test_lds_resident_kernel_gemm_every_wave_split(rm, oracle, split, M, K, N):
-    """Plain GEMMs with short K run as 1x1 layers of the LDS-resident kernel, in every wave split."""
+    """Plain GEMMs with short K run as 1x1 layers of the LDS-resident kernel, in every wave split;
+    K = 576 and 1152 (nine times 64 / 128) run through the 3x3 families as convolutions over N
+    images of 3x3 pixels."""
     rng = np.random.default_rng(M + K + N + sum(split))
     W = si.weights_rowscaled(rng, M, K)
     scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, 35, 60, 5))
@@ -204,10 +206,36 @@ def test_first_layer_kernel_several_tiles_per_work_group(rm, oracle, B, k, pad):
     _check_conv(rm, oracle, geom, 40, (35, 60, 5), 8, 2, True, True, 32, "first_layer")
 
 
+def test_gemm_with_k_of_a_lowered_3x3_layer_four_bit_output(rm, oracle):
+    """K = 576 = 9 x 64 through the 3x3 family, 4-bit output with bias and ReLU and without (the lean
+    epilogue), ragged N."""
+    rng = np.random.default_rng(576)
+    M, K, N = 96, 576, 333
+    W = si.weights_rowscaled(rng, M, K)
+    scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, 35, 60, 5))
+    xq = si.act_codes_u4(rng, (N, K))
+    ref = oracle.quantize_rows(W, scheme)
+    acc = oracle.gemm_acc(ref["wint"], xq.astype(np.int32))
+    p = rm.rmsmp_pack_weights(W, scheme)
+    X = _to_dev(rm.pack_u4(xq))
+    for z, with_bias in ((0, False), (4, True)):
+        bias = rng.normal(0.0, 0.3, M).astype(np.float32) if with_bias else None
+        _, y, _ = oracle.epilogue(acc, oracle.rowsum(ref["wint"]), z, ref["rowscale"], 0.05, bias, True)
+        inv = np.float32(15.0 / float(np.percentile(y, 99.0)))
+        _, _, q = oracle.epilogue(acc, oracle.rowsum(ref["wint"]), z, ref["rowscale"], 0.05, bias, True, inv)
+        Yq = torch.full((N, M // 2), 0xEE, dtype=torch.uint8, device=DEV)
+        rm.rmsmp_gemm(p, X, N, rm.make_epilogue(0.05, z, 4, None if bias is None else _to_dev(bias), True, rm.OUT_U4, inv), Yq)
+        assert rm.rmsmp_debug_last_dispatch()[0] == "lds_resident"
+        torch.cuda.synchronize()
+        assert np.array_equal(_grouped_codes(rm, Yq.cpu().numpy(), p.perm), q)
+    p.free()
+
+
 def test_dispatch_record_names_the_kernel(rm, oracle):
     """The dispatch hook reports the kernel family of the last launch on this thread."""
     rng = np.random.default_rng(5)
-    for (M, K, N, want) in [(64, 4096, 8, "skinny"), (64, 512, 256, "lds_resident"), (37, 130, 77, "general")]:
+    for (M, K, N, want) in [(64, 4096, 8, "skinny"), (64, 512, 256, "lds_resident"), (64, 576, 256, "lds_resident"),
+                            (37, 130, 77, "general")]:
         W = si.weights_rowscaled(rng, M, K)
         scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, 35, 60, 5))
         xq = si.act_codes_u4(rng, (N, K))
