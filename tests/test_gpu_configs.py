@@ -86,7 +86,10 @@ def test_config4_skinny_gemm(rm, oracle, N):
     p.free()
 
 
-def _resnet_layer(rm, oracle, idx, B, n_samples, structured=False):
+def _layer_reference(rm, oracle, idx, B, n_samples, structured=False, x=None):
+    """Packed weights of layer idx of the ResNet-18 stack and the oracle's accumulators and 4-bit
+    codes at sampled outputs.  x: input codes to use instead of the layer's own seeded ones (the
+    shortcut projection of a stage reads the input of the stage's first 3x3 layer)."""
     name, C, M, k, s, pad, H = si.RESNET18_CONVS[idx]
     rng = si.rng_for(3, idx)
     K = C * k * k
@@ -98,7 +101,9 @@ def _resnet_layer(rm, oracle, idx, B, n_samples, structured=False):
         bits = 8
     else:
         scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, 35, 60, 5))
-        x, s_x, bits = si.act_codes_u4(rng, (B, H, H, C)), 0.05, 4
+        s_x, bits = 0.05, 4
+        if x is None:
+            x = si.act_codes_u4(rng, (B, H, H, C))
     p = rm.rmsmp_pack_weights(Wt, scheme, taps=k * k)
     d = rm.ConvDesc(B, C, H, H, k, k, s, pad)
     od = oracle.conv_desc(B, C, H, H, k, k, s, pad)
@@ -141,6 +146,24 @@ def _resnet_layer(rm, oracle, idx, B, n_samples, structured=False):
         sel = ms == r
         _, _, qq = oracle.epilogue(acc_s[sel][None, :], rs[r:r + 1], 0, ref["rowscale"][r:r + 1], s_x, None, True, inv)
         q_ref[sel] = qq[0]
+    return dict(name=name, p=p, d=d, x=x, s_x=s_x, bits=bits, M=M, N=N, ms=ms, ns=ns, acc_s=acc_s, q_ref=q_ref, inv=inv)
+
+
+def _check_samples(R, Yi, Yq):
+    ms, ns, M, p = R["ms"], R["ns"], R["M"], R["p"]
+    got_acc = Yi[torch.from_numpy(ms).to(DEV), torch.from_numpy(ns).to(DEV)].cpu().numpy()
+    assert np.array_equal(got_acc, R["acc_s"]), R["name"]
+    inv_perm = np.empty(M, np.int64)
+    inv_perm[p.perm] = np.arange(M)
+    g = inv_perm[ms]
+    bytes_ = Yq[torch.from_numpy(ns).to(DEV), torch.from_numpy(g // 2).to(DEV)].cpu().numpy()
+    got_q = np.where(g % 2 == 0, bytes_ & 15, bytes_ >> 4).astype(np.uint8)
+    assert np.array_equal(got_q, R["q_ref"]), R["name"]
+
+
+def _resnet_layer(rm, oracle, idx, B, n_samples, structured=False):
+    R = _layer_reference(rm, oracle, idx, B, n_samples, structured)
+    p, d, x, s_x, bits, M, N, inv = (R[k] for k in ("p", "d", "x", "s_x", "bits", "M", "N", "inv"))
     X = _dev(rm.pack_u4(x) if bits == 4 else x)
     ws_bytes = rm.rmsmp_conv2d_workspace_size(p, d, bits)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV) if ws_bytes else None
@@ -149,16 +172,43 @@ def _resnet_layer(rm, oracle, idx, B, n_samples, structured=False):
     Yq = torch.empty((N, M // 2), dtype=torch.uint8, device=DEV)
     rm.rmsmp_conv2d(p, X, d, rm.make_epilogue(s_x, 0, bits, None, True, rm.OUT_U4, inv), Yq, ws)
     torch.cuda.synchronize()
-    got_acc = Yi[torch.from_numpy(ms).to(DEV), torch.from_numpy(ns).to(DEV)].cpu().numpy()
-    assert np.array_equal(got_acc, acc_s), name
-    inv_perm = np.empty(M, np.int64)
-    inv_perm[p.perm] = np.arange(M)
-    g = inv_perm[ms]
-    bytes_ = Yq[torch.from_numpy(ns).to(DEV), torch.from_numpy(g // 2).to(DEV)].cpu().numpy()
-    got_q = np.where(g % 2 == 0, bytes_ & 15, bytes_ >> 4).astype(np.uint8)
-    assert np.array_equal(got_q, q_ref), name
+    _check_samples(R, Yi, Yq)
     p.free()
     del Yi, Yq, X, ws
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("head", ["layer2.0", "layer3.0", "layer4.0"])
+def test_config3_stage_heads_as_one_launch_batch64_sampled(rm, oracle, head):
+    """The launches bench.py makes for the head of stages 2-4 at batch 64: the stride-2 3x3
+    convolution and the stride-2 1x1 shortcut projection on the same input through
+    rmsmp_conv2d_pair, accumulators and 4-bit codes of both against the oracle on the same
+    structured and random samples as the single layers."""
+    names = [c[0] for c in si.RESNET18_CONVS]
+    ia, ib = names.index(head + ".conv1"), names.index(head + ".downsample")
+    A = _layer_reference(rm, oracle, ia, 64, 4000, structured=True)
+    Bl = _layer_reference(rm, oracle, ib, 64, 4000, structured=True, x=A["x"])
+    X = _dev(rm.pack_u4(A["x"]))
+    out = {}
+    for kind in (rm.OUT_INT32, rm.OUT_U4):
+        Ys = []
+        eps = []
+        for R in (A, Bl):
+            if kind == rm.OUT_INT32:
+                Ys.append(torch.empty((R["M"], R["N"]), dtype=torch.int32, device=DEV))
+                eps.append(rm.make_epilogue(R["s_x"], 0, 4, None, False, kind))
+            else:
+                Ys.append(torch.empty((R["N"], R["M"] // 2), dtype=torch.uint8, device=DEV))
+                eps.append(rm.make_epilogue(R["s_x"], 0, 4, None, True, kind, R["inv"]))
+        rm.rmsmp_conv2d_pair(A["p"], A["d"], eps[0], Ys[0], Bl["p"], Bl["d"], eps[1], Ys[1], X)
+        assert rm.rmsmp_debug_last_dispatch()[0] == "lds_resident_pair"
+        out[kind] = Ys
+    torch.cuda.synchronize()
+    _check_samples(A, out[rm.OUT_INT32][0], out[rm.OUT_U4][0])
+    _check_samples(Bl, out[rm.OUT_INT32][1], out[rm.OUT_U4][1])
+    A["p"].free()
+    Bl["p"].free()
+    del out, X
     torch.cuda.empty_cache()
 
 
