@@ -22,7 +22,10 @@ WIDE_PAIR_SOURCE = "csrc/patch_wide_pair.hip"
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed-FP32 VALU forms are kept off (per-lane fp32 epilogue must be bit-reproducible)
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-ffp-contract=off", "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc")]
+         "-ffp-contract=off",
+         # leading scalar kernel arguments arrive in registers at wave launch instead of through a
+         # first read of the argument block (the wide and the skinny kernels are written for it)
+         "-mllvm", "-amdgpu-kernarg-preload-count=14", "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc")]
 
 
 def _units():

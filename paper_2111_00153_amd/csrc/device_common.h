@@ -225,13 +225,15 @@ __device__ __forceinline__ void requant_block(const v16i& v, const float (&m)[16
 // over inside the kernel arguments): for y at or above the minimum of GELU the code is the largest
 // c with rise[c] <= y, searched downwards from the code y itself would get (never too low, since
 // GELU(y) <= max(y, 0)); below the minimum it is fall_base plus the number of fall[j] >= y.
-// The kernel arguments start with the GemmArgs block in every kernel of the library.
+// KOFF: byte offset of the GemmArgs block inside the kernel arguments (0 unless the kernel takes
+// leading scalar arguments in front of it).
+template <int KOFF = 0>
 __device__ __forceinline__ void gelu_requant_block(const v16i& v, const float (&m)[16], const float (&bias)[16], float inv_s,
                                                    int z_out, uint32_t (&packed)[2]) {
   // (the table is read in place: scalar loads for the wave-uniform fields, a per-lane load for rise[code])
   typedef const __attribute__((address_space(4))) char karg_char;
   typedef const __attribute__((address_space(4))) GeluTable karg_table;
-  karg_table* const tab = (karg_table*)((karg_char*)__builtin_amdgcn_kernarg_segment_ptr() + __builtin_offsetof(GemmArgs, gelu));
+  karg_table* const tab = (karg_table*)((karg_char*)__builtin_amdgcn_kernarg_segment_ptr() + KOFF + __builtin_offsetof(GemmArgs, gelu));
   const float y_split = tab->y_split;
   const int fix_steps = tab->fix_steps, fall_base = tab->fall_base, n_fall = tab->n_fall;
   const RMSMP_GLOBAL float* const rise = (const RMSMP_GLOBAL float*)(uintptr_t)tab->rise;
@@ -289,7 +291,7 @@ __device__ __forceinline__ void gelu_requant_block(const v16i& v, const float (&
 // float(16 a) * (m / 16) and float(a) * m are the same float, because scaling by a power of two
 // commutes with rounding.
 // GELU: whether the calling kernel carries the GELU epilogue (out_kind 3) at all.
-template <int NB, class Meta, bool GELU = true>
+template <int NB, class Meta, bool GELU = true, int KOFF = 0>
 __device__ __forceinline__ void finish_tiles(const EpArgs& a, int kind, const v16i (&acc)[NB], const Meta& rm,
                                              int n_rows, const int64_t (&n)[NB]) {
   if (n_rows <= 0) return;
@@ -353,7 +355,7 @@ __device__ __forceinline__ void finish_tiles(const EpArgs& a, int kind, const v1
   uint32_t packed[NB][2];
   if (GELU && out_kind == 3) {
 #pragma unroll
-    for (int j = 0; j < NB; ++j) gelu_requant_block(v[j], m, bias, a.out_inv_scale, a.out_zero_point, packed[j]);
+    for (int j = 0; j < NB; ++j) gelu_requant_block<KOFF>(v[j], m, bias, a.out_inv_scale, a.out_zero_point, packed[j]);
   } else {
 #pragma unroll
   for (int j = 0; j < NB; ++j) {

@@ -186,26 +186,42 @@ static int launch_general(const GemmArgs& a, hipStream_t s) {
 constexpr int SK_THREADS = 512;
 constexpr int SK_WAVES = 8;
 constexpr int SK_CHUNK = 16;  // K steps whose loads are in flight together per wave
+typedef unsigned sk_v2w __attribute__((ext_vector_type(2)));
+typedef unsigned sk_v4w __attribute__((ext_vector_type(4)));
+
+// What a wave needs before it can issue its weight and activation reads, fetched from the kernel
+// arguments in one go at the start of the kernel.
+struct SkinnyFirst {
+  const uint8_t* blob;
+  const void* X;
+  const uint32_t* p_lut;
+  int nks, ldx, N;
+};
 
 template <int KIND, int NB>
-__device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, const TileRef& tr, int mt) {
+__device__ __forceinline__ void skinny_body(const SkinnyFirst& f, const GemmArgs& a, uint8_t* smem, const TileRef& tr, int mt) {
   RMSMP_REG_STAMPS_DECLARE();
   RMSMP_REG_STAMP(0);
-  const EpArgs ea = pin_epilogue_args(a);
+  EpArgs ea{};  // fetched once the first reads are on their way (the argument block comes from memory)
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   constexpr int FRAG = KIND == TILE_I8 ? 16 : 8;
   constexpr int ROWS = 32 * NB;
-  const int nks = a.w.nks;
+  const int nks = f.nks;
   const int S = (nks + SK_WAVES - 1) / SK_WAVES;  // K steps per wave
   const int ks0 = wave * S;
-  const uint8_t* wbase = a.w.blob + tr.blob_off;
+  // Weights and activations are read through buffer descriptors: the K-step offset of a weight
+  // read and the column offset of an activation read are scalar, the per-lane offsets are formed
+  // once, and a read past the end returns zeros (whose products are never used), so the reads at
+  // the start of the kernel -- which run at the speed of instruction fetch, one wave of a SIMD
+  // after the other -- cost one instruction each instead of a 64-bit address each.
+  const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void*)(f.blob + tr.blob_off), 0, nks * (LANES * FRAG), 0x00020000);
   const uint32_t wl = (uint32_t)lane * FRAG;
   uint4 T = make_uint4(0, 0, 0, 0);
-  if (KIND == TILE_NIB_LUT) T = *(const uint4*)(a.w.p_lut + ((int64_t)mt * TILE_M + tile_row_goff(lane & 31)) * 4);
-  const uint8_t* X = (const uint8_t*)a.X;
-  const int64_t ldx = a.K / 2;
+  if (KIND == TILE_NIB_LUT) T = *(const uint4*)(f.p_lut + ((int64_t)mt * TILE_M + tile_row_goff(lane & 31)) * 4);
+  const int ldx = f.ldx;
+  const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void*)f.X, 0, f.N * ldx, 0x00020000);
   const int x_stride = SK_CHUNK * 16 + 8;  // LDS bytes per activation row of a chunk (padded)
   uint8_t* xs = smem + wave * (ROWS * x_stride);
 
@@ -224,24 +240,32 @@ __device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, co
     typename RawFrag<KIND>::type raw[SK_CHUNK];
 #pragma unroll
     for (int u = 0; u < SK_CHUNK; ++u) {
-      int ks = ks0 + c0 + u;
-      ks = ks < nks ? ks : nks - 1;
-      raw[u] = load_raw<KIND>(wbase + (int64_t)ks * (LANES * FRAG), wl);
-    }
-    constexpr int XI = ROWS * SK_CHUNK / LANES;
-    uint4 xw[XI];
-    {
-      const int64_t col0 = (int64_t)(ks0 + c0) * 16;  // byte offset inside an activation row
-#pragma unroll
-      for (int i = 0; i < XI; ++i) {
-        const int pidx = i * LANES + lane;
-        const int row = pidx / SK_CHUNK, piece = pidx % SK_CHUNK;
-        const int64_t n = row < (int)a.N ? row : (int)a.N - 1;  // rows past N repeat the last one; never stored
-        int64_t cb = col0 + piece * 16;
-        cb = cb + 16 <= ldx ? cb : ldx - 16;  // past the end of K: any data, its weights are zero
-        xw[i] = *(const uint4*)(X + n * ldx + cb);
+      const int soff = (ks0 + c0 + u) * (LANES * FRAG);  // past the end of the tile: zeros
+      if constexpr (KIND == TILE_I8) {
+        const sk_v4w w = __builtin_amdgcn_raw_buffer_load_b128(wrs, (int)wl, soff, 0);
+        raw[u] = make_uint4(w.x, w.y, w.z, w.w);
+      } else {
+        const sk_v2w w = __builtin_amdgcn_raw_buffer_load_b64(wrs, (int)wl, soff, 0);
+        raw[u] = make_uint2(w.x, w.y);
       }
     }
+    constexpr int XI = ROWS * SK_CHUNK / LANES;
+    static_assert(LANES % SK_CHUNK == 0, "a lane keeps its piece number over the reads of a chunk");
+    uint4 xw[XI];
+    {
+      const int col0 = (ks0 + c0) * 16;  // byte offset inside an activation row (scalar)
+      const int piece = lane % SK_CHUNK, row0 = lane / SK_CHUNK;
+      const int n_last = f.N - 1;
+#pragma unroll
+      for (int i = 0; i < XI; ++i) {
+        const int row = i * (LANES / SK_CHUNK) + row0;
+        const int n = row < n_last ? row : n_last;  // rows past N repeat the last one; never stored
+        // (past the end of K: whatever follows in the tensor or zeros, its weights are zero)
+        const sk_v4w w = __builtin_amdgcn_raw_buffer_load_b128(xrs, n * ldx + piece * 16, col0, 0);
+        xw[i] = make_uint4(w.x, w.y, w.z, w.w);
+      }
+    }
+    if (c0 == 0) ea = pin_epilogue_args(a);
     RMSMP_REG_STAMP(1);
 #pragma unroll
     for (int i = 0; i < XI; ++i) {
@@ -317,23 +341,27 @@ __device__ __forceinline__ void skinny_body(const GemmArgs& a, uint8_t* smem, co
 template <int NB>
 __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
-  // Every kernel argument the kernel will read, asked for here: left to itself the compiler fetches
+  // Every kernel argument the first reads need, asked for here: left to itself the compiler fetches
   // an argument where it is first used, which puts half a dozen dependent scalar-memory round trips
-  // in front of the first weight read; this way they are one.
-  asm volatile("" ::"s"(a.w.blob), "s"(a.w.p_meta), "s"(a.w.p_lut), "s"(a.w.nks), "s"(a.w.class_tiles[0]), "s"(a.w.class_tiles[1]),
+  // in front of the first weight read; this way they are one.  (Handing them over in registers at
+  // wave launch -- kernel-argument preloading, which the wide kernels use -- delays the launch of
+  // this kernel's eight waves per work-group by more than it saves: 6.7 -> 7.2 us.)
+  asm volatile("" ::"s"(a.w.blob), "s"(a.w.p_lut), "s"(a.w.nks), "s"(a.w.class_tiles[0]), "s"(a.w.class_tiles[1]),
                "s"(a.w.class_rows[0]), "s"(a.w.class_rows[1]), "s"(a.w.class_rows[2]), "s"(a.K), "s"(a.N), "s"(a.X));
   const int mt = blockIdx.x;
   const TileRef tr = tile_ref(a.w, mt);
+  const SkinnyFirst f{a.w.blob, a.X, a.w.p_lut, a.w.nks, (int)(a.K / 2), (int)a.N};
   if (tr.kind == TILE_NIB_SHIFT)
-    skinny_body<TILE_NIB_SHIFT, NB>(a, smem_raw, tr, mt);
+    skinny_body<TILE_NIB_SHIFT, NB>(f, a, smem_raw, tr, mt);
   else if (tr.kind == TILE_NIB_LUT)
-    skinny_body<TILE_NIB_LUT, NB>(a, smem_raw, tr, mt);
+    skinny_body<TILE_NIB_LUT, NB>(f, a, smem_raw, tr, mt);
   else
-    skinny_body<TILE_I8, NB>(a, smem_raw, tr, mt);
+    skinny_body<TILE_I8, NB>(f, a, smem_raw, tr, mt);
 }
 
 static bool skinny_applies(const GemmArgs& a) {
-  return !a.conv && a.ep.act_bits == 4 && a.N <= 64 && a.K % 64 == 0 && a.K >= 512;
+  // (K below 2^24: the kernel's byte offsets into X and into a weight tile are 32-bit)
+  return !a.conv && a.ep.act_bits == 4 && a.N <= 64 && a.K % 64 == 0 && a.K >= 512 && a.K < ((int64_t)1 << 24);
 }
 
 template <int NB>

@@ -42,6 +42,9 @@
 namespace rmsmp {
 
 constexpr int PW_THREADS = 256;
+// bytes of leading scalar kernel arguments in front of the GemmArgs block (WIDE_FIRST_PARAMS below: twelve 4-byte slots)
+constexpr int WIDE_FIRST_BYTES = 48;
+static_assert(alignof(GemmArgs) <= 8, "the GemmArgs block must start right after the leading arguments");
 constexpr int PW_PATCH_UNROLL = 6;  // 16-byte patch pieces in flight per thread, at most
 // The patches of the 3x3 layers at hand are just under five pieces per thread (128 pixels plus halo
 // x 8 pieces, 512 + halo x 2, ...), those of the 1x1 layers / GEMMs exactly six (64 x 24): a batch
@@ -590,7 +593,7 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
         for (int o = 0; o < BPT; ++o) {
           const int64_t ncol[1] = {col0 + 32 * o};
           const v16i blocks[1] = {mine[ti * BPT + o]};
-          finish_tiles<1, RowMetaLds, true>(ea, kind, blocks, rm, n_rows, ncol);
+          finish_tiles<1, RowMetaLds, true, WIDE_FIRST_BYTES>(ea, kind, blocks, rm, n_rows, ncol);
         }
         continue;
       }
@@ -612,37 +615,62 @@ __device__ __forceinline__ void wide_wave(const GemmArgs& a, const EpArgs& ea, c
 
 // block_id: the work-group's number within its layer (the launch's own work-group id, except in a
 // launch that carries two layers)
+// What a work-group needs before it can issue the reads of its input patch.  The kernels take
+// these as leading scalar arguments (WIDE_FIRST_PARAMS), which the hardware hands over in
+// registers at wave launch (kernel-argument preloading, -mllvm -amdgpu-kernarg-preload-count):
+// the first read of the argument block from memory costs 450-700 cycles at the start of every
+// launch, and nothing else can run before it.  The same values are in GemmArgs / WideGeom.
+struct WideFirst {
+  const void* X;
+  int gx, gy;
+  uint32_t magic_hw, magic_ow;
+  int H, W, OH, OW, stride, pad, gather, B, pix_bytes;
+  int64_t N;
+};
+#define WIDE_FIRST_PARAMS                                                                                         \
+  const void *f_X, int f_gx, int f_gy, uint32_t f_magic_hw, uint32_t f_magic_ow, uint32_t f_hw, uint32_t f_ohw, \
+      uint32_t f_spg, int f_B, int f_pix_bytes, int f_N
+#define WIDE_FIRST_UNPACK()                                                                                   \
+  WideFirst {                                                                                                 \
+    f_X, f_gx, f_gy, f_magic_hw, f_magic_ow, (int)(f_hw & 0xffffu), (int)(f_hw >> 16), (int)(f_ohw & 0xffffu), \
+        (int)(f_ohw >> 16), (int)(f_spg & 0xffu), (int)((f_spg >> 8) & 0xffu), (int)(f_spg >> 16), f_B,       \
+        f_pix_bytes, (int64_t)f_N                                                                             \
+  }
+__device__ __forceinline__ WideFirst wide_first_of(const GemmArgs& a, const WideGeom& g) {
+  return WideFirst{a.X, g.gx, g.gy, g.magic_hw, g.magic_ow, a.d.H, a.d.W, a.OH, a.OW, a.d.stride, a.d.pad, g.gather, a.d.B, g.pix_bytes, a.N};
+}
+
 template <int TAPS, int CPT, int XB, int KS, int NWT, int MS, bool DEEP>
-__device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGeom& g, const unsigned block_id) {
+__device__ __forceinline__ void wide_kernel_impl(const WideFirst& f, const GemmArgs& a, const WideGeom& g, const unsigned block_id) {
   RMSMP_PHASE(0);
   // Work-group id -> (pixel tile bx, row block by).  Consecutive ids go to different XCDs, each
   // with its own L2, so the gy work-groups that read the same input patch get ids that are equal
   // modulo 8 and follow each other on that XCD: the patch comes out of memory once, not gy
   // times.  The grid is padded to a multiple of 8 pixel tiles; the extra work-groups leave.
   const int xcd = block_id & 7, slot = block_id >> 3;
-  const int by = slot % g.gy;
-  const int bx = (slot / g.gy) * 8 + xcd;
-  if (bx >= g.gx) return;
+  const int by = slot % f.gy;
+  const int bx = (slot / f.gy) * 8 + xcd;
+  if (bx >= f.gx) return;
   // first of all, the reads of the input patch: they depend on nothing but the pixel tile
   WidePatchLoads pl;
   {
     const int n0 = bx * (32 * XB * NWT);
-    const int hw_out = a.OH * a.OW;
-    const int b = wide_fast_div(n0, g.magic_hw);
+    const int hw_out = f.OH * f.OW;
+    const int b = wide_fast_div(n0, f.magic_hw);
     const int rem = n0 - b * hw_out;
-    const int oh = wide_fast_div(rem, g.magic_ow);
-    const int ow = rem - oh * a.OW;
-    int f_lo = (b * a.d.H + (oh * a.d.stride - a.d.pad)) * a.d.W + (ow * a.d.stride - a.d.pad);
+    const int oh = wide_fast_div(rem, f.magic_ow);
+    const int ow = rem - oh * f.OW;
+    int f_lo = (b * f.H + (oh * f.stride - f.pad)) * f.W + (ow * f.stride - f.pad);
     f_lo = f_lo < 0 ? 0 : f_lo;
-    const uint32_t x_bytes = (uint32_t)(a.d.B * a.d.H * a.d.W) * (uint32_t)g.pix_bytes;
+    const uint32_t x_bytes = (uint32_t)(f.B * f.H * f.W) * (uint32_t)f.pix_bytes;
     pl.f_lo = f_lo;
-    pl.xr = wide_rsrc((const uint8_t*)a.X, x_bytes);
-    pl.src0 = (uint32_t)f_lo * (uint32_t)g.pix_bytes;
-    pl.chunked = DEEP, pl.pix_bytes = g.pix_bytes;
+    pl.xr = wide_rsrc((const uint8_t*)f.X, x_bytes);
+    pl.src0 = (uint32_t)f_lo * (uint32_t)f.pix_bytes;
+    pl.chunked = DEEP, pl.pix_bytes = f.pix_bytes;
     pl.x_last = x_bytes - 16u;
-    pl.gather = TAPS == 1 ? g.gather : 0, pl.n0 = n0, pl.n_last = (int)a.N - 1, pl.hw_out = hw_out, pl.OW = a.OW;
-    pl.H = a.d.H, pl.W = a.d.W, pl.S = a.d.stride, pl.magic_hw = g.magic_hw, pl.magic_ow = g.magic_ow;
-    if (TAPS == 1 && g.gather) pl.f_lo = 0;
+    pl.gather = TAPS == 1 ? f.gather : 0, pl.n0 = n0, pl.n_last = (int)f.N - 1, pl.hw_out = hw_out, pl.OW = f.OW;
+    pl.H = f.H, pl.W = f.W, pl.S = f.stride, pl.magic_hw = f.magic_hw, pl.magic_ow = f.magic_ow;
+    if (TAPS == 1 && f.gather) pl.f_lo = 0;
 #pragma unroll
     for (int u = 0; u < pw_batch(TAPS); ++u) pl.pw[u] = wide_load_piece<CPT>(pl, u * (LANES * KS * NWT * MS) + (int)threadIdx.x);
   }
@@ -670,8 +698,8 @@ __device__ __forceinline__ void wide_kernel_impl(const GemmArgs& a, const WideGe
 }
 
 template <int TAPS, int CPT, int XB, int KS, int NWT, int MS, bool DEEP>
-__global__ __launch_bounds__(LANES * KS * NWT * MS, KS * NWT * MS == 8 ? 1 : 2) void conv_wide_kernel(GemmArgs a, WideGeom g) {
-  wide_kernel_impl<TAPS, CPT, XB, KS, NWT, MS, DEEP>(a, g, blockIdx.x);
+__global__ __launch_bounds__(LANES * KS * NWT * MS, KS * NWT * MS == 8 ? 1 : 2) void conv_wide_kernel(WIDE_FIRST_PARAMS, GemmArgs a, WideGeom g) {
+  wide_kernel_impl<TAPS, CPT, XB, KS, NWT, MS, DEEP>(WIDE_FIRST_UNPACK(), a, g, blockIdx.x);
 }
 
 // Two layers that read the same input tensor as one launch: a 3x3 layer and a 1x1 layer with the
@@ -692,12 +720,13 @@ constexpr WidePairSplit wide_pair_split(int cpt) {
 }
 
 template <int CPT>
-__global__ __launch_bounds__(LANES * 4, 2) void conv_wide_pair_kernel(GemmArgs a, WideGeom ga, GemmArgs b, WideGeom gb, unsigned blocks_a) {
+__global__ __launch_bounds__(LANES * 4, 2) void conv_wide_pair_kernel(WIDE_FIRST_PARAMS, GemmArgs a, WideGeom ga, GemmArgs b, WideGeom gb, unsigned blocks_a) {
+  // (the leading arguments are the 3x3 layer's; the 1x1 layer's work-groups read theirs from memory)
   constexpr WidePairSplit sp = wide_pair_split(CPT);
   if (blockIdx.x < blocks_a)
-    wide_kernel_impl<9, CPT, sp.xa, sp.ka, sp.na, sp.ma, false>(a, ga, blockIdx.x);
+    wide_kernel_impl<9, CPT, sp.xa, sp.ka, sp.na, sp.ma, false>(WIDE_FIRST_UNPACK(), a, ga, blockIdx.x);
   else
-    wide_kernel_impl<1, CPT, sp.xb, sp.kb, sp.nb, sp.mb, false>(b, gb, blockIdx.x - blocks_a);
+    wide_kernel_impl<1, CPT, sp.xb, sp.kb, sp.nb, sp.mb, false>(wide_first_of(b, gb), b, gb, blockIdx.x - blocks_a);
 }
 
 struct WidePlan {
@@ -709,6 +738,14 @@ struct WidePlan {
   int cpt = 0;  // K steps of 32 channels staged at a time (the kernel family)
 };
 
+// the leading scalar arguments of a launch, from its plan (sizes are checked by the host: image
+// sides below 2^16, stride and padding below 2^8, pixel counts below 2^23)
+#define WIDE_FIRST_ARGS(p)                                                                                              \
+  (p).a.X, (p).g.gx, (p).g.gy, (p).g.magic_hw, (p).g.magic_ow, (uint32_t)(p).a.d.H | ((uint32_t)(p).a.d.W << 16),        \
+      (uint32_t)(p).a.OH | ((uint32_t)(p).a.OW << 16),                                                                  \
+      (uint32_t)(p).a.d.stride | ((uint32_t)(p).a.d.pad << 8) | ((uint32_t)(p).g.gather << 16), (int)(p).a.d.B,        \
+      (p).g.pix_bytes, (int)(p).a.N
+
 template <int TAPS, int CPT, int XB, int KS, int NWT, int MS, bool DEEP>
 inline int launch_wide_t(const WidePlan& p, hipStream_t s) {
   if constexpr (CPT % KS != 0 || TAPS * (CPT / KS) < 2) {
@@ -716,7 +753,7 @@ inline int launch_wide_t(const WidePlan& p, hipStream_t s) {
   } else {
     static std::atomic<uint64_t> allowed{0};
     if (const int rc = allow_large_lds((const void*)conv_wide_kernel<TAPS, CPT, XB, KS, NWT, MS, DEEP>, allowed)) return rc;
-    hipLaunchKernelGGL((conv_wide_kernel<TAPS, CPT, XB, KS, NWT, MS, DEEP>), dim3(p.blocks), dim3(LANES * KS * NWT * MS), p.lds, s, p.a, p.g);
+    hipLaunchKernelGGL((conv_wide_kernel<TAPS, CPT, XB, KS, NWT, MS, DEEP>), dim3(p.blocks), dim3(LANES * KS * NWT * MS), p.lds, s, WIDE_FIRST_ARGS(p), p.a, p.g);
     return (int)hipGetLastError();
   }
 }
@@ -726,7 +763,7 @@ inline int launch_wide_pair_t(const WidePlan& pa, const WidePlan& pb, hipStream_
   static std::atomic<uint64_t> allowed{0};
   if (const int rc = allow_large_lds((const void*)conv_wide_pair_kernel<CPT>, allowed)) return rc;
   const size_t lds = pa.lds > pb.lds ? pa.lds : pb.lds;
-  hipLaunchKernelGGL((conv_wide_pair_kernel<CPT>), dim3(pa.blocks + pb.blocks), dim3(LANES * 4), lds, s, pa.a, pa.g, pb.a, pb.g, pa.blocks);
+  hipLaunchKernelGGL((conv_wide_pair_kernel<CPT>), dim3(pa.blocks + pb.blocks), dim3(LANES * 4), lds, s, WIDE_FIRST_ARGS(pa), pa.a, pa.g, pb.a, pb.g, pa.blocks);
   return (int)hipGetLastError();
 }
 

@@ -61,6 +61,8 @@ static bool wide_plan_mode(const GemmArgs& a, int cc, int xb, int ks, int nwt, i
   if (in_px + span >= ((int64_t)1 << 31) / rs) return false;
   // 24-bit multiplications in the kernel's pixel index arithmetic
   if (in_px + span >= ((int64_t)1 << 23) || a.N + bn >= ((int64_t)1 << 23) || hw >= ((int64_t)1 << 23)) return false;
+  // image sides, stride and padding travel packed in the kernels' leading arguments
+  if (a.d.H >= 65536 || a.d.W >= 65536 || a.OH >= 65536 || a.OW >= 65536 || a.d.stride >= 256 || a.d.pad >= 256) return false;
   // 24-bit LDS address arithmetic
   const size_t need = (size_t)(span + 1) * rs;  // patch + zero-point row
   const size_t xch = (size_t)pw_xch_bytes(xb, ks, ks * nwt * ms);
