@@ -9,6 +9,8 @@
 // how a tile is decoded.  Accumulation is int32 and exact.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "device_common.h"
 
 namespace rmsmp {
@@ -209,6 +211,7 @@ __device__ __forceinline__ void skinny_body(const SkinnyFirst& f, const GemmArgs
   constexpr int FRAG = KIND == TILE_I8 ? 16 : 8;
   constexpr int ROWS = 32 * NB;
   const int nks = f.nks;
+  const bool few = f.N <= ROWS / 2;  // at most half of the columns exist: leave the other activation reads out
   const int S = (nks + SK_WAVES - 1) / SK_WAVES;  // K steps per wave
   const int ks0 = wave * S;
   // Weights and activations are read through buffer descriptors: the K-step offset of a weight
@@ -256,19 +259,31 @@ __device__ __forceinline__ void skinny_body(const SkinnyFirst& f, const GemmArgs
       const int col0 = (ks0 + c0) * 16;  // byte offset inside an activation row (scalar)
       const int piece = lane % SK_CHUNK, row0 = lane / SK_CHUNK;
       const int n_last = f.N - 1;
+      // A read covers LANES / SK_CHUNK rows.  With fewer than ROWS columns the reads whose rows all
+      // lie past N are left out (their LDS rows keep whatever they hold: columns past N are computed
+      // and never stored); with all of them the reads are unconditional, in one batch.
+      auto read_x = [&](auto few_tag) {
+        constexpr bool FEW = decltype(few_tag)::value;
 #pragma unroll
-      for (int i = 0; i < XI; ++i) {
-        const int row = i * (LANES / SK_CHUNK) + row0;
-        const int n = row < n_last ? row : n_last;  // rows past N repeat the last one; never stored
-        // (past the end of K: whatever follows in the tensor or zeros, its weights are zero)
-        const sk_v4w w = __builtin_amdgcn_raw_buffer_load_b128(xrs, n * ldx + piece * 16, col0, 0);
-        xw[i] = make_uint4(w.x, w.y, w.z, w.w);
-      }
+        for (int i = 0; i < XI; ++i) {
+          if (FEW && i * (LANES / SK_CHUNK) > n_last) continue;
+          const int row = i * (LANES / SK_CHUNK) + row0;
+          const int n = row < n_last ? row : n_last;
+          // (past the end of K: whatever follows in the tensor or zeros, its weights are zero)
+          const sk_v4w w = __builtin_amdgcn_raw_buffer_load_b128(xrs, n * ldx + piece * 16, col0, 0);
+          xw[i] = make_uint4(w.x, w.y, w.z, w.w);
+        }
+      };
+      if (few)
+        read_x(std::true_type{});
+      else
+        read_x(std::false_type{});
     }
     if (c0 == 0) ea = pin_epilogue_args(a);
     RMSMP_REG_STAMP(1);
 #pragma unroll
     for (int i = 0; i < XI; ++i) {
+      if (few && i * (LANES / SK_CHUNK) > f.N - 1) continue;
       const int pidx = i * LANES + lane;
       const int row = pidx / SK_CHUNK, piece = pidx % SK_CHUNK;
       *(uint2*)(xs + row * x_stride + piece * 16) = make_uint2(xw[i].x, xw[i].y);
