@@ -116,7 +116,9 @@ __device__ __forceinline__ TileRef tile_ref(const DevicePacked& w, int mt) {
     idx = mt - t0 - t1;
     t.blob_off = (int64_t)(t0 + t1) * nib_tile + (int64_t)idx * i8_tile;
   }
-  const int left = w.class_rows[t.kind] - idx * TILE_M;
+  // (selected, not indexed: an index into the kernel arguments would be one more dependent read)
+  const int rows0 = w.class_rows[0], rows1 = w.class_rows[1], rows2 = w.class_rows[2];
+  const int left = (t.kind == TILE_NIB_SHIFT ? rows0 : t.kind == TILE_NIB_LUT ? rows1 : rows2) - idx * TILE_M;
   t.nvalid = left < TILE_M ? left : TILE_M;
   return t;
 }
