@@ -90,6 +90,22 @@ rmsmp_status rmsmp_pack_weights(const float* W, int64_t M, int64_t K, const uint
                                 const float* alpha, int32_t taps, const int32_t* in_perm,
                                 rmsmp_packed** out);
 
+/*
+ * rmsmp_pack_weights with storage options.  flags = 0 is rmsmp_pack_weights.
+ *   RMSMP_PACK_POT_AS_INT8  PoT-4 rows are stored decoded, one byte per weight (their level
+ *       2^(6-k) or 0, signed), like Fixed-8 rows: the same levels, scales and results bit for
+ *       bit, twice the weight bytes for those rows, and no table decode in the K loop.  On
+ *       matrix cores a PoT row multiplies at the same rate as any other and only its decode
+ *       costs (the opposite of Section 4's FPGA, where PoT rows are the cheap ones), so this
+ *       pays for compute-bound layers -- convolutions, GEMMs with many columns -- and costs
+ *       bandwidth where the weights are the traffic (N <= 64).
+ * Errors: as rmsmp_pack_weights, plus EINVAL for an unknown flag.
+ */
+#define RMSMP_PACK_POT_AS_INT8 1u
+rmsmp_status rmsmp_pack_weights_opt(const float* W, int64_t M, int64_t K, const uint8_t* scheme,
+                                    const float* alpha, int32_t taps, const int32_t* in_perm,
+                                    uint32_t flags, rmsmp_packed** out);
+
 void rmsmp_free_packed(rmsmp_packed* p);
 
 /*

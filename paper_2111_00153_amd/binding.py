@@ -55,7 +55,7 @@ EXPORTS = ["rmsmp_last_error", "rmsmp_version", "rmsmp_ratio_counts", "rmsmp_ass
            "rmsmp_pack_roundtrip_host", "rmsmp_gemm", "rmsmp_conv2d", "rmsmp_conv2d_workspace_size",
            "rmsmp_fake_quant_rows", "rmsmp_ste_backward", "rmsmp_debug_set_wave_split",
            "rmsmp_debug_last_dispatch", "rmsmp_debug_measure_peaks", "rmsmp_init", "rmsmp_conv2d_static_workspace", "rmsmp_debug_gelu_breakpoints",
-           "rmsmp_conv2d_pair"]
+           "rmsmp_conv2d_pair", "rmsmp_pack_weights_opt"]
 
 
 def _check(rc):
@@ -133,7 +133,11 @@ class Packed:
             pass
 
 
-def rmsmp_pack_weights(W, scheme, alpha=None, taps=1, in_perm=None):
+PACK_POT_AS_INT8 = 1  # RMSMP_PACK_POT_AS_INT8
+
+
+def rmsmp_pack_weights(W, scheme, alpha=None, taps=1, in_perm=None, flags=0):
+    """flags = 0: rmsmp_pack_weights; otherwise rmsmp_pack_weights_opt with those flags."""
     W = _np(W, np.float32)
     M, K = W.shape
     scheme = _np(scheme, np.uint8)
@@ -142,8 +146,12 @@ def rmsmp_pack_weights(W, scheme, alpha=None, taps=1, in_perm=None):
     alpha = None if alpha is None else _np(alpha, np.float32)
     in_perm = None if in_perm is None else _np(in_perm, np.int32)
     h = ctypes.c_void_p()
-    _check(_lib.rmsmp_pack_weights(_ptr(W), ctypes.c_int64(M), ctypes.c_int64(K), _ptr(scheme), _ptr(alpha),
-                                   ctypes.c_int32(taps), _ptr(in_perm), ctypes.byref(h)))
+    if flags:
+        _check(_lib.rmsmp_pack_weights_opt(_ptr(W), ctypes.c_int64(M), ctypes.c_int64(K), _ptr(scheme), _ptr(alpha),
+                                           ctypes.c_int32(taps), _ptr(in_perm), ctypes.c_uint32(flags), ctypes.byref(h)))
+    else:
+        _check(_lib.rmsmp_pack_weights(_ptr(W), ctypes.c_int64(M), ctypes.c_int64(K), _ptr(scheme), _ptr(alpha),
+                                       ctypes.c_int32(taps), _ptr(in_perm), ctypes.byref(h)))
     return Packed(h, M, K, taps)
 
 

@@ -103,14 +103,20 @@ rmsmp_status rmsmp_assign_by_variance(const float* W, int64_t M, int64_t K, int6
 
 rmsmp_status rmsmp_pack_weights(const float* W, int64_t M, int64_t K, const uint8_t* scheme, const float* alpha,
                                 int32_t taps, const int32_t* in_perm, rmsmp_packed** out) {
+  return rmsmp_pack_weights_opt(W, M, K, scheme, alpha, taps, in_perm, 0u, out);
+}
+
+rmsmp_status rmsmp_pack_weights_opt(const float* W, int64_t M, int64_t K, const uint8_t* scheme, const float* alpha,
+                                    int32_t taps, const int32_t* in_perm, uint32_t flags, rmsmp_packed** out) {
   if (!out) return fail(RMSMP_EINVAL, "pack_weights: out is NULL");
+  if (flags & ~RMSMP_PACK_POT_AS_INT8) return fail(RMSMP_EINVAL, "pack_weights: unknown flag");
   *out = nullptr;
   rmsmp_packed* p = new (std::nothrow) rmsmp_packed();
   if (!p) return fail(RMSMP_ENOMEM, "pack_weights: host allocation failed");
   std::string err;
   rmsmp_status st;
   try {
-    st = rmsmp::pack_host(W, M, K, scheme, alpha, taps, in_perm, &p->host, &err);
+    st = rmsmp::pack_host(W, M, K, scheme, alpha, taps, in_perm, &p->host, &err, flags);
   } catch (const std::bad_alloc&) {
     delete p;
     return fail(RMSMP_ENOMEM, "pack_weights: host allocation failed");

@@ -130,7 +130,7 @@ rmsmp_status assign_by_variance(const float* W, int64_t M, int64_t K, int64_t n_
 }
 
 rmsmp_status pack_host(const float* W, int64_t M, int64_t K, const uint8_t* scheme, const float* alpha_in,
-                       int32_t taps, const int32_t* in_perm, HostPacked* hp, std::string* err) {
+                       int32_t taps, const int32_t* in_perm, HostPacked* hp, std::string* err, uint32_t flags) {
   if (!W || !scheme || !hp) {
     *err = "pack_weights: NULL argument";
     return RMSMP_EINVAL;
@@ -235,10 +235,13 @@ rmsmp_status pack_host(const float* W, int64_t M, int64_t K, const uint8_t* sche
   // and scales do not change, and the layer needs ceil(M / TILE_M) tiles instead of up to two more.
   // Every class then starts at a multiple of TILE_M in grouped order (two grouped rows share
   // one byte of the 4-bit output, so class boundaries must at least be even).
+  // With RMSMP_PACK_POT_AS_INT8 the PoT-4 rows are stored decoded, one byte per level: the same
+  // levels and scales, twice the bytes, and nothing to decode in the kernels' K loops.
+  const bool pot_bytes = (flags & RMSMP_PACK_POT_AS_INT8) != 0;
   std::vector<int32_t> cls((size_t)M);
   for (int64_t r = 0; r < M; ++r)
-    cls[(size_t)r] = scheme[r] == RMSMP_FIXED4 ? TILE_NIB_SHIFT : scheme[r] == RMSMP_POT4 ? TILE_NIB_LUT : TILE_I8;
-  int64_t n_cls[3] = {hp->counts[0], hp->counts[1], hp->counts[2]};
+    cls[(size_t)r] = scheme[r] == RMSMP_FIXED4 ? TILE_NIB_SHIFT : (scheme[r] == RMSMP_POT4 && !pot_bytes) ? TILE_NIB_LUT : TILE_I8;
+  int64_t n_cls[3] = {hp->counts[0], pot_bytes ? 0 : hp->counts[1], hp->counts[2] + (pot_bytes ? hp->counts[1] : 0)};
   for (int c = 0; c < 2; ++c) {
     int64_t spill = n_cls[c] % TILE_M;
     if (spill == 0) continue;

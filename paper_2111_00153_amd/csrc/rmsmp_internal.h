@@ -77,7 +77,7 @@ struct HostPacked {
 // Host side of rmsmp_pack_weights: quantize, encode, group, lay out.  Returns RMSMP_OK or an
 // error with `err` filled.
 rmsmp_status pack_host(const float* W, int64_t M, int64_t K, const uint8_t* scheme, const float* alpha,
-                       int32_t taps, const int32_t* in_perm, HostPacked* out, std::string* err);
+                       int32_t taps, const int32_t* in_perm, HostPacked* out, std::string* err, uint32_t flags = 0);
 
 // Decode a blob (as laid out by pack_host) back to integer weights in original order.
 void unpack_host(const HostPacked& hp, const uint8_t* blob, int8_t* wint);

@@ -247,3 +247,57 @@ def test_dispatch_record_names_the_kernel(rm, oracle):
         ref = oracle.quantize_rows(W, scheme)
         assert np.array_equal(Y.cpu().numpy(), oracle.gemm_acc(ref["wint"], xq.astype(np.int32)))
         p.free()
+
+
+@pytest.mark.parametrize("ratio", [(35, 60, 5), (100, 0, 0)])
+def test_pot_rows_stored_as_int8_give_the_same_results(rm, oracle, ratio):
+    """RMSMP_PACK_POT_AS_INT8: PoT-4 rows stored decoded.  Codes, scales, row sums, accumulators and
+    4-bit outputs are those of the oracle (and so of the 4-bit storage) through the LDS-resident, the
+    skinny and the general kernel."""
+    rng = np.random.default_rng(800 + ratio[0])
+    # a 3x3 layer (LDS-resident kernel)
+    B, C, H, M = 3, 128, 12, 160
+    K = C * 9
+    Wt = si.weights_rowscaled(rng, M, K)
+    scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, *ratio))
+    x = si.act_codes_u4(rng, (B, H, H, C))
+    ref = oracle.quantize_rows(Wt, scheme)
+    p = rm.rmsmp_pack_weights(Wt, scheme, taps=9, flags=rm.PACK_POT_AS_INT8)
+    p4 = rm.rmsmp_pack_weights(Wt, scheme, taps=9)
+    assert p.counts == p4.counts  # the schemes are what they were; only the storage differs
+    assert np.array_equal(rm.rmsmp_unpack_codes(p).astype(np.int32), ref["wint"])
+    assert np.array_equal(p.rowscale, ref["rowscale"]) and np.array_equal(p.rowsum, oracle.rowsum(ref["wint"]))
+    od = oracle.conv_desc(B, C, H, H, 3, 3, 1, 1)
+    acc = oracle.conv_acc(ref["wint"].reshape(M, C, 3, 3), x.astype(np.int32), od, zpad=2)
+    rs = oracle.rowsum(ref["wint"])
+    acc_c, y, _ = oracle.epilogue(acc, rs, 2, ref["rowscale"], 0.05, None, True)
+    inv = np.float32(15.0 / float(np.percentile(y, 99.0)))
+    _, _, q = oracle.epilogue(acc, rs, 2, ref["rowscale"], 0.05, None, True, inv)
+    X = _to_dev(rm.pack_u4(x))
+    d = rm.ConvDesc(B, C, H, H, 3, 3, 1, 1)
+    N = B * H * H
+    Y = torch.full((M, N), -777, dtype=torch.int32, device=DEV)
+    rm.rmsmp_conv2d(p, X, d, rm.make_epilogue(0.05, 2, 4, None, False, rm.OUT_INT32), Y)
+    assert rm.rmsmp_debug_last_dispatch()[0] == "lds_resident"
+    Yq = torch.full((N, M // 2), 0xEE, dtype=torch.uint8, device=DEV)
+    rm.rmsmp_conv2d(p, X, d, rm.make_epilogue(0.05, 2, 4, None, True, rm.OUT_U4, inv), Yq)
+    torch.cuda.synchronize()
+    assert np.array_equal(Y.cpu().numpy(), acc_c)
+    assert np.array_equal(_grouped_codes(rm, Yq.cpu().numpy(), p.perm), q)
+    p.free()
+    p4.free()
+    # plain GEMMs: skinny (N = 8) and general (K = 130 fits no other kernel)
+    for (M, K, N, want) in [(96, 1024, 8, "skinny"), (70, 130, 77, "general")]:
+        Wt = si.weights_rowscaled(rng, M, K)
+        scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, *ratio))
+        xq = si.act_codes_u4(rng, (N, K))
+        ref = oracle.quantize_rows(Wt, scheme)
+        p = rm.rmsmp_pack_weights(Wt, scheme, flags=rm.PACK_POT_AS_INT8)
+        Y = torch.full((M, N), -777, dtype=torch.int32, device=DEV)
+        rm.rmsmp_gemm(p, _to_dev(rm.pack_u4(xq)), N, rm.make_epilogue(0.05, 0, 4, None, False, rm.OUT_INT32), Y)
+        assert rm.rmsmp_debug_last_dispatch()[0] == want
+        torch.cuda.synchronize()
+        assert np.array_equal(Y.cpu().numpy(), oracle.gemm_acc(ref["wint"], xq.astype(np.int32)))
+        p.free()
+    with pytest.raises(rm.RmsmpError):
+        rm.rmsmp_pack_weights(Wt, scheme, flags=6)
