@@ -34,8 +34,9 @@ def _conv_out(h, k, s, p):
     return (h + 2 * p - k) // s + 1
 
 
-def make_stack(rm, si, torch, dev, batch, inv_scales=None):
-    """Synthetic ResNet-18 conv stack: packed weights, resident inputs, output buffers, launchers."""
+def make_stack(rm, si, torch, dev, batch, inv_scales=None, pack_flags=0, reuse=None):
+    """Synthetic ResNet-18 conv stack: packed weights, resident inputs, output buffers, launchers.
+    reuse: a stack built earlier whose input tensors this one shares (same seeds, same values)."""
     layers = []
     by_name = {}
     for idx, (name, C, M, k, s, pad, H) in enumerate(si.RESNET18_CONVS):
@@ -49,12 +50,14 @@ def make_stack(rm, si, torch, dev, batch, inv_scales=None):
         else:
             scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, 35, 60, 5))
             s_x, bits = 0.05, 4
-            x = None if name.endswith(".downsample") else si.act_codes_u4(rng, (batch, H, H, C))
+            x = None if name.endswith(".downsample") or reuse is not None else si.act_codes_u4(rng, (batch, H, H, C))
         OH = _conv_out(H, k, s, pad)
         N = batch * OH * OH
-        p = rm.rmsmp_pack_weights(W, scheme, taps=k * k)
+        p = rm.rmsmp_pack_weights(W, scheme, taps=k * k, flags=pack_flags)
         d = rm.ConvDesc(batch, C, H, H, k, k, s, pad)
-        if x is None:
+        if reuse is not None:
+            x, X = reuse[idx]["x"], reuse[idx]["X"]
+        elif x is None:
             # the 1x1 projection of a stage's shortcut reads the stage's input: the tensor of its first 3x3 layer
             head = by_name[name.replace(".downsample", ".conv1")]
             x, X = head["x"], head["X"]
@@ -289,6 +292,46 @@ def two_stream_schedule(rm, torch, layers, steps, warm):
                     "(the headline is the one-stream step that the kernel trace and the per-layer times describe)"}
 
 
+def pot_rows_as_int8(rm, si, torch, dev, layers, steps, warm):
+    """The same one-stream step with the PoT-4 rows of every layer stored decoded, one byte per
+    weight (RMSMP_PACK_POT_AS_INT8): same levels, scales and output codes, no table decode in the
+    K loop, twice the bytes for those rows.  The codes of every layer are compared, in original row
+    order, with what the headline step left in its buffers."""
+    alt = make_stack(rm, si, torch, dev, BATCH, [L["inv"] for L in layers], rm.PACK_POT_AS_INT8, reuse=layers)
+    launchers = [u["launch"] for u in launch_units(rm, alt)]
+
+    def step():
+        for f in launchers:
+            f()
+
+    def codes(L):  # [N][M] in original row order
+        g = torch.stack((L["Y"] & 15, L["Y"] >> 4), dim=2).reshape(L["N"], L["M"])
+        out = torch.empty_like(g)
+        out[:, torch.from_numpy(np.asarray(L["p"].perm, dtype=np.int64)).to(g.device)] = g
+        return out
+
+    for _ in range(warm):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    same = all(bool(torch.equal(codes(a), codes(b))) for a, b in zip(alt, layers))
+    if not same:
+        raise SystemExit("bench.py: the step with PoT rows stored as int8 gives other codes than the headline step")
+    ops = sum(L["ops"] for L in layers)
+    wbytes = [sum(cnt * L["K"] * b for cnt, b in zip(L["p"].counts, fac)) for L in layers[1:] for fac in ((0.5, 0.5, 1.0), (0.5, 1.0, 1.0))]
+    for L in alt:
+        L["p"].free()
+    return {"ms_per_step": round(ms, 6), "tops": round(ops / (ms * 1e-3) / 1e12, 2),
+            "pct_of_int8_mfma_peak": round(100.0 * ops / (ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, 2),
+            "codes_identical_to_headline_step": same,
+            "weight_bytes_mixed_layers": {"nibble_storage": int(sum(wbytes[0::2])), "pot_as_int8": int(sum(wbytes[1::2]))},
+            "note": "not the headline: the headline keeps both 4-bit schemes nibble-packed and decodes PoT codes in registers"}
+
+
 def traffic_from_profile(kernel_name):
     """HBM bytes per launch of the dominant kernel as the committed rocprofv3 counter summary of this
     workload states them (a counter cannot be read from inside this script); None when no summary
@@ -437,6 +480,7 @@ def main():
     }
     if not args.no_extras:
         out["two_stream_schedule"] = two_stream_schedule(rm, torch, layers, args.steps, args.warmup)
+        out["pot_rows_stored_as_int8"] = pot_rows_as_int8(rm, si, torch, dev, layers, args.steps, args.warmup)
         out["other_configs"] = other_configs(rm, si, torch, dev)
         mfma_tops, copy_gbs = rm.rmsmp_debug_measure_peaks()
         out["measured_peaks"] = {"mfma_only_int8_tops": round(mfma_tops, 1), "stream_copy_gbs": round(copy_gbs, 1),
