@@ -171,6 +171,15 @@ def test_argument_errors(rm):
                 assert e.value.code == 1
 
 
+def test_pack_options_reject_unknown_flags(rm):
+    """rmsmp_pack_weights_opt checks its flags before it touches the GPU."""
+    W = np.ones((4, 8), np.float32)
+    for flags in (2, 6, 1 << 31):
+        with pytest.raises(rm.RmsmpError) as e:
+            rm.rmsmp_pack_weights(W, np.zeros(4, np.uint8), flags=flags)
+        assert e.value.code == 1
+
+
 def test_nibble_helpers(rm):
     c = np.arange(32, dtype=np.uint8).reshape(2, 16) % 16
     b = rm.pack_u4(c)
