@@ -332,6 +332,90 @@ def pot_rows_as_int8(rm, si, torch, dev, layers, steps, warm):
             "note": "not the headline: the headline keeps both 4-bit schemes nibble-packed and decodes PoT codes in registers"}
 
 
+def chained_step(rm, oracle, si, torch, dev, layers, steps, warm):
+    """The same 17 launches with every layer from layer1.0.conv2 on reading the 4-bit tensor the
+    layer before it wrote (a stage's first 3x3 layer and its shortcut projection read the previous
+    stage's output; residual adds and pooling are outside the path, so conv1 does not feed layer1).
+    A layer writes its codes in grouped row order and the next layer's weights are packed with
+    in_perm = that order, so nothing is shuffled between the launches.  With the oracle at hand it
+    runs the same chain on the first and the last image first -- the output scale of every layer is
+    the 99.9th percentile of its own output there, so that the chain stays alive -- and the codes
+    of every layer, up to 19 chained layers deep, are compared bit for bit."""
+    def producer(name):
+        stage, block, conv = name.split(".")
+        if conv == "conv2":
+            return "%s.%s.conv1" % (stage, block)
+        if block == "1":
+            return "%s.0.conv2" % stage
+        return None if stage == "layer1" else "layer%d.1.conv2" % (int(stage[5:]) - 1)
+
+    imgs = [0, BATCH - 1]
+    want, inv_of, hist = {}, {}, None
+    if oracle is not None:
+        out = {}
+        for L in layers[1:]:
+            src = producer(L["name"])
+            x = L["x"][imgs] if src is None else out[src]
+            ref = oracle.quantize_rows(L["W"], L["scheme"], want_levels=False)
+            k, M = L["k"], L["M"]
+            d = oracle.conv_desc(len(imgs), L["C"], L["H"], L["H"], k, k, L["s"], L["pad"])
+            acc = oracle.conv_acc(ref["wint"].reshape(M, L["C"], k, k), x.astype(np.int32), d, 0)
+            rs = oracle.rowsum(ref["wint"])
+            _, y, _ = oracle.epilogue(acc, rs, 0, ref["rowscale"], L["s_x"], None, True)
+            inv = np.float32(15.0 / max(float(np.percentile(y, 99.9)), 1e-6))
+            _, _, q = oracle.epilogue(acc, rs, 0, ref["rowscale"], L["s_x"], None, True, inv)
+            want[L["name"]], inv_of[L["name"]] = q, inv
+            out[L["name"]] = np.ascontiguousarray(q.T).reshape(len(imgs), L["OH"], L["OH"], M).astype(np.uint8)  # NHWC, original channel order
+            hist = np.bincount(q.ravel(), minlength=16).tolist()
+
+    chain = []
+    for L in layers:
+        src = None if L["idx"] == 0 else producer(L["name"])
+        C = dict(L)
+        if src is not None:
+            P = next(c for c in chain if c["name"] == src)
+            C["p"] = rm.rmsmp_pack_weights(L["W"], L["scheme"], taps=L["k"] * L["k"], in_perm=P["p"].perm)
+            C["X"] = P["Y"].view(BATCH, L["H"], L["H"], L["C"] // 2)
+            C["own_pack"] = True
+        if L["name"] in inv_of:
+            C["ep"] = rm.make_epilogue(L["s_x"], 0, L["bits"], None, True, rm.OUT_U4, inv_of[L["name"]])
+        C["Y"] = torch.empty_like(L["Y"])
+        chain.append(C)
+    launchers = [u["launch"] for u in launch_units(rm, chain)]
+
+    def step():
+        for f in launchers:
+            f()
+
+    for _ in range(warm):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    checked = None
+    if oracle is not None:
+        for C in chain[1:]:
+            q, M, hw = want[C["name"]], C["M"], C["OH"] * C["OH"]
+            Y = C["Y"].view(BATCH, hw, M // 2)[torch.tensor(imgs)].reshape(len(imgs) * hw, M // 2).cpu().numpy()
+            got = np.empty_like(q)
+            got[C["p"].perm] = rm.unpack_u4(Y).T
+            if not np.array_equal(got, q):
+                raise SystemExit("bench.py: chained step: GPU output of %s differs from the oracle" % C["name"])
+        checked = ("every layer of the chain equals the oracle's chain on images 0 and %d; code counts of the last layer there: %s"
+                   % (BATCH - 1, hist))
+    ops = sum(L["ops"] for L in layers)
+    for C in chain:
+        if C.get("own_pack"):
+            C["p"].free()
+    return {"ms_per_step": round(ms, 6), "tops": round(ops / (ms * 1e-3) / 1e12, 2), "launches_per_step": len(launchers),
+            "checked": checked,
+            "note": "layers 2..20 read the previous layer's 4-bit output (grouped row order, next weights packed with in_perm); "
+                    "not the headline: the headline's layers read independent synthetic tensors of the workload's distribution"}
+
+
 def traffic_from_profile(kernel_name):
     """HBM bytes per launch of the dominant kernel as the committed rocprofv3 counter summary of this
     workload states them (a counter cannot be read from inside this script); None when no summary
@@ -480,6 +564,7 @@ def main():
     }
     if not args.no_extras:
         out["two_stream_schedule"] = two_stream_schedule(rm, torch, layers, args.steps, args.warmup)
+        out["chained_step"] = chained_step(rm, oracle if base is not None else None, si, torch, dev, layers, args.steps, args.warmup)
         out["pot_rows_stored_as_int8"] = pot_rows_as_int8(rm, si, torch, dev, layers, args.steps, args.warmup)
         out["other_configs"] = other_configs(rm, si, torch, dev)
         mfma_tops, copy_gbs = rm.rmsmp_debug_measure_peaks()

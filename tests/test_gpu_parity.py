@@ -344,6 +344,49 @@ def test_chained_layers_through_grouped_order(rm, oracle):
     p2.free()
 
 
+def test_chained_convolutions_through_grouped_order(rm, oracle):
+    """Three 3x3 layers and a shortcut projection chained on the GPU: every layer reads the 4-bit
+    tensor the layer before it wrote (grouped row order; its weights are packed with in_perm = that
+    order), the stride-2 layer and the 1x1 projection go out as one rmsmp_conv2d_pair.  The codes of
+    every layer must be the oracle's, which works in the original channel order throughout."""
+    rng = np.random.default_rng(4242)
+    B, H = 3, 12
+    spec = [("a", 64, 64, 3, 1, 1, None), ("b", 64, 128, 3, 2, 1, "a"), ("side", 64, 128, 1, 2, 0, "a"), ("c", 128, 128, 3, 1, 1, "b")]
+    x0 = si.act_codes_u4(rng, (B, H, H, 64))
+    ref_out, gpu = {}, {}
+    for name, C, M, k, s, pad, src in spec:
+        Hin = H if src in (None, "a") else H // 2
+        OH = (Hin + 2 * pad - k) // s + 1
+        W = si.weights_rowscaled(rng, M, C * k * k)
+        scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, 35, 60, 5))
+        x = x0 if src is None else ref_out[src]
+        ref = oracle.quantize_rows(W, scheme)
+        od = oracle.conv_desc(B, C, Hin, Hin, k, k, s, pad)
+        acc = oracle.conv_acc(ref["wint"].reshape(M, C, k, k), x.astype(np.int32), od, 0)
+        rs = oracle.rowsum(ref["wint"])
+        _, y, _ = oracle.epilogue(acc, rs, 0, ref["rowscale"], 0.05, None, True)
+        inv = np.float32(15.0 / max(float(np.percentile(y, 99.0)), 1e-6))
+        _, _, q = oracle.epilogue(acc, rs, 0, ref["rowscale"], 0.05, None, True, inv)
+        assert len(np.unique(q)) > 8  # the chain stays alive: most codes occur
+        ref_out[name] = np.ascontiguousarray(q.T).reshape(B, OH, OH, M).astype(np.uint8)
+        p = rm.rmsmp_pack_weights(W, scheme, taps=k * k, in_perm=None if src is None else gpu[src]["p"].perm)
+        X = _to_dev(rm.pack_u4(x0)) if src is None else gpu[src]["Y"].view(B, Hin, Hin, C // 2)
+        Y = torch.full((B * OH * OH, M // 2), 0xEE, dtype=torch.uint8, device=DEV)
+        gpu[name] = dict(p=p, X=X, Y=Y, q=q, d=rm.ConvDesc(B, C, Hin, Hin, k, k, s, pad),
+                         ep=rm.make_epilogue(0.05, 0, 4, None, True, rm.OUT_U4, inv))
+    g = gpu
+    rm.rmsmp_conv2d(g["a"]["p"], g["a"]["X"], g["a"]["d"], g["a"]["ep"], g["a"]["Y"])
+    rm.rmsmp_conv2d_pair(g["b"]["p"], g["b"]["d"], g["b"]["ep"], g["b"]["Y"], g["side"]["p"], g["side"]["d"], g["side"]["ep"], g["side"]["Y"], g["b"]["X"])
+    rm.rmsmp_conv2d(g["c"]["p"], g["c"]["X"], g["c"]["d"], g["c"]["ep"], g["c"]["Y"])
+    torch.cuda.synchronize()
+    for name in g:
+        got = np.empty_like(g[name]["q"])
+        got[g[name]["p"].perm] = rm.unpack_u4(g[name]["Y"].cpu().numpy()).T
+        assert np.array_equal(got, g[name]["q"]), name
+    for name in g:
+        g[name]["p"].free()
+
+
 def test_empty_and_errors(rm):
     W = np.ones((4, 8), np.float32)
     p = rm.rmsmp_pack_weights(W, np.array([0, 1, 2, 0], np.uint8))
