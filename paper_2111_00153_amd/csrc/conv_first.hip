@@ -341,12 +341,60 @@ __global__ __launch_bounds__(256, 3) void conv_first_kernel(GemmArgs a, FirstGeo
         };
         // (mine_live is the same for the whole wave: every lane feeds the MFMAs)
         if constexpr (MODE == 1) {
-          // all four blocks in one piece of straight-line code: the LDS reads, MFMAs and requantization
-          // of different blocks overlap, and the number of stores in flight is known where the next
-          // tile's pixels are waited for
+          // All four blocks in one piece of straight-line code, software-pipelined: the MFMA chain of
+          // block bl + 1 (seven dependent instructions, each waiting for the one before) is issued
+          // between the vector instructions that requantize block bl, so the wave's matrix work runs
+          // in the shadow of its own vector work (the waves of a SIMD pass the per-tile barrier
+          // together and would otherwise all be in their MFMA chains, then all in their epilogues).
           if (mine_live) {
+            auto frags = [&](const int bl, v4i (&bf)[KHW]) {
+              const int oh_l = 8 * (wave >> 1) + 2 * bl + pr;
+              const uint8_t* fp = buf + (oh_l * 2) * CF_ROWB + (pc + 2 * hh + pos.shift) * 8;
 #pragma unroll
-            for (int bl = 0; bl < 4; ++bl) do_block(bl);
+              for (int kh = 0; kh < KHW; ++kh) {
+                const uint2 lo = *(const uint2*)(fp + kh * CF_ROWB);
+                const uint2 hi = *(const uint2*)(fp + kh * CF_ROWB + 8);
+                bf[kh] = (v4i){(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
+              }
+            };
+            auto chain = [&](const v4i (&bf)[KHW]) -> v16i {
+              v16i acc;
+#pragma unroll
+              for (int r = 0; r < 16; ++r) acc[r] = 0;
+#pragma unroll
+              for (int kh = 0; kh < KHW; ++kh) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(av[kh], bf[kh], acc, 0, 0, 0);
+              return acc;
+            };
+            auto finish = [&](const int bl, const v16i& acc) {
+              uint32_t packed[2];
+              float brow[16];
+              requant_block<false, false>(acc, mkeep, brow, ea.out_inv_scale, packed);
+              const int oh = pos.oh0 + 8 * (wave >> 1) + 2 * bl + pr;
+              const int s_off = s_tile + (8 * (wave >> 1) + 2 * bl) * s_row;
+              __builtin_amdgcn_raw_buffer_store_b64((v2u){packed[0], packed[1]}, yr, (col_ok && oh < a.OH) ? lane_off : (int)0x80000000, s_off, 0);
+            };
+            v4i bf0[KHW], bf1[KHW];
+            frags(0, bf0);
+            v16i cur = chain(bf0);
+            frags(1, bf1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int bl = 0; bl < 4; ++bl) {
+              v16i nxt = cur;
+              if (bl + 1 < 4) nxt = chain((bl & 1) ? bf0 : bf1);
+              if (bl + 2 < 4) frags(bl + 2, (bl & 1) ? bf1 : bf0);
+              finish(bl, cur);
+              if (bl + 1 < 4) {
+                // one MFMA of the next block's chain behind every dozen vector instructions of this block's epilogue
+#pragma unroll
+                for (int kh = 0; kh < KHW; ++kh) {
+                  __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+                  __builtin_amdgcn_sched_group_barrier(0x002, 12, 0);  // VALU
+                }
+              }
+              __builtin_amdgcn_sched_barrier(0);
+              cur = nxt;
+            }
           }
         } else {
 #pragma unroll 1
