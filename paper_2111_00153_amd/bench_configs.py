@@ -73,7 +73,7 @@ def gemm_case(cfg, M, K, N, ratio, out_kind, z=0, copies=1, label=""):
     return us
 
 
-def conv_case(cfg, idx, B, geom=None, M=None, ratio=(35, 60, 5), quiet=False):
+def conv_case(cfg, idx, B, geom=None, M=None, ratio=(35, 60, 5), quiet=False, pack_flags=0):
     if geom is None:
         name, C, M, k, s, pad, H = si.RESNET18_CONVS[idx]
     else:
@@ -89,7 +89,7 @@ def conv_case(cfg, idx, B, geom=None, M=None, ratio=(35, 60, 5), quiet=False):
         scheme = si.scheme_permutation(rng, rm.rmsmp_ratio_counts(M, *ratio))
         bits = 4
         X = torch.from_numpy(rm.pack_u4(si.act_codes_u4(rng, (B, H, H, C)))).to(DEV)
-    p = rm.rmsmp_pack_weights(W, scheme, taps=k * k)
+    p = rm.rmsmp_pack_weights(W, scheme, taps=k * k, flags=pack_flags)
     d = rm.ConvDesc(B, C, H, H, k, k, s, pad)
     OH = (H + 2 * pad - k) // s + 1
     N = B * OH * OH
@@ -110,17 +110,21 @@ TABLE6_RATIOS = [(0, 100, 0), (100, 0, 0), (50, 50, 0), (60, 40, 0), (67, 33, 0)
 
 
 def ratio_sweep():
-    """Throughput against the scheme ratio (Table 6's rows) on configs[1] and on the ResNet-18 stack.
+    """Throughput against the scheme ratio (Table 6's rows) on configs[1] and on the ResNet-18 stack,
+    with PoT rows nibble-packed (decoded in registers) and with PoT rows stored as int8.
     On matrix cores every scheme multiplies at the same rate; what changes is the decode work."""
     for ratio in TABLE6_RATIOS:
-        us1, ops1 = conv_case(1, 0, 32, geom=("configs[1] %d:%d:%d" % ratio, 256, 3, 1, 1, 14), M=256, ratio=ratio)
-        tot_us = tot_ops = 0.0
-        for i in range(len(si.RESNET18_CONVS)):
-            us, ops = conv_case(3, i, 64, ratio=ratio, quiet=True)
-            tot_us += us
-            tot_ops += ops
+        res = []
+        for flags in (0, rm.PACK_POT_AS_INT8):
+            us1, ops1 = conv_case(1, 0, 32, geom=("configs[1] %d:%d:%d" % ratio, 256, 3, 1, 1, 14), M=256, ratio=ratio, quiet=True, pack_flags=flags)
+            tot_us = tot_ops = 0.0
+            for i in range(len(si.RESNET18_CONVS)):
+                us, ops = conv_case(3, i, 64, ratio=ratio, quiet=True, pack_flags=flags)
+                tot_us += us
+                tot_ops += ops
+            res.append((us1, ops1 / us1 / 1e6, tot_us / 1e3, tot_ops / tot_us / 1e6))
         print("sweep PoT4:Fixed4:Fixed8 = %3d:%3d:%2d   configs[1] %6.2f us %7.1f TOPS   ResNet-18 stack %.3f ms %6.1f TOPS"
-              % (ratio + (us1, ops1 / us1 / 1e6, tot_us / 1e3, tot_ops / tot_us / 1e6)), flush=True)
+              "   | PoT rows as int8: configs[1] %6.2f us %7.1f TOPS   stack %.3f ms %6.1f TOPS" % (ratio + res[0] + res[1]), flush=True)
 
 
 def extra_layers():
